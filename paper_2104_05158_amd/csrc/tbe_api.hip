@@ -1,0 +1,637 @@
+// Host side of the table-batched embedding-bag library: handle, workspace carve-up, launch
+// geometry and the extern "C" entry points declared in include/tbe.h.
+//
+// Section 5.1 of arxiv 2104.05158 asks for one forward launch and one fused backward+optimizer
+// step for all tables of a GPU; here the forward is literally one kernel and the backward is a
+// fixed sequence (key build, radix sort passes, run-length, fused reduce+AdaGrad, long-run fix-up)
+// enqueued on the caller's stream without any host synchronisation.
+#include "tbe.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "tbe_kernels.hip.h"
+
+using namespace tbe;
+
+namespace {
+
+enum Slot {
+    SLOT_FORWARD = 0,
+    SLOT_BUILD_KEYS,
+    SLOT_RADIX_HIST,
+    SLOT_RADIX_SCAN,
+    SLOT_RADIX_SCATTER,
+    SLOT_RUNLENGTH,
+    SLOT_REDUCE_UPDATE,
+    SLOT_LONG_FIXUP,
+    SLOT_COUNT
+};
+const char* const kSlotNames[SLOT_COUNT] = {"forward",       "build_keys", "radix_hist",    "radix_scan",
+                                            "radix_scatter", "runlength",  "reduce_update", "long_fixup"};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int pow2ceil_log2(int x)
+{
+    int l = 0;
+    while ((1 << l) < x)
+        ++l;
+    return l;
+}
+
+struct ProfRec {
+    int slot;
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct tbe_s {
+    int T = 0;
+    std::vector<int64_t> rows;
+    std::vector<int32_t> dims;
+    int dtype = 0;
+    int max_batch = 0;
+    int64_t max_indices = 0;
+    int64_t sumD = 0;
+    int dmax = 0;
+    int fwd_epl = 4;
+    int fwd_kmax = 1;
+    int key_bits = 1;
+    std::vector<int64_t> woff;      // T+1, elements
+    std::vector<int64_t> soff;      // T+1, rows
+    std::vector<int32_t> coloff;    // T+1
+    std::vector<TableMeta> meta;
+
+    // workspace layout (byte offsets)
+    size_t off_meta = 0, off_rowbase = 0, off_counters = 0, off_keys[2] = {0, 0}, off_vals[2] = {0, 0};
+    size_t off_hist = 0, off_scan_tmp = 0, off_rl_counts = 0, off_chunk_first = 0, off_partials = 0;
+    size_t off_long_list = 0, workspace_bytes = 0;
+    size_t weight_bytes = 0, state_bytes = 0;
+
+    // bound buffers
+    void* d_weights = nullptr;
+    float* d_state = nullptr;
+    char* d_ws = nullptr;
+    bool bound = false;
+    int final_buf = -1;  // which (keys, vals) pair holds the sorted result of the last backward
+
+    // profiling
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
+    std::vector<ProfRec> recs;
+    bool profiling = false;
+
+    std::string last_hip_error;
+
+    template <typename P>
+    P* ws(size_t off) const
+    {
+        return reinterpret_cast<P*>(d_ws + off);
+    }
+};
+
+namespace {
+
+struct ScopedTimer {
+    tbe_s* h;
+    hipStream_t st;
+    ProfRec rec;
+    bool on = false;
+    ScopedTimer(tbe_s* h_, int slot, hipStream_t st_) : h(h_), st(st_)
+    {
+        if (h->profiling && h->ev_used + 2 <= h->ev_pool.size()) {
+            rec.slot = slot;
+            rec.start = h->ev_pool[h->ev_used++];
+            rec.stop = h->ev_pool[h->ev_used++];
+            on = hipEventRecord(rec.start, st) == hipSuccess;
+        }
+    }
+    ~ScopedTimer()
+    {
+        if (on && hipEventRecord(rec.stop, st) == hipSuccess)
+            h->recs.push_back(rec);
+    }
+};
+
+tbe_status_t hip_fail(tbe_s* h, hipError_t e, const char* what)
+{
+    if (h)
+        h->last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return TBE_ERR_HIP;
+}
+
+#define TBE_HIP_CHECK(h, expr)                     \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess)                      \
+            return hip_fail((h), e_, #expr);       \
+    } while (0)
+
+#define TBE_LAUNCH_CHECK(h, what)                  \
+    do {                                           \
+        hipError_t e_ = hipGetLastError();         \
+        if (e_ != hipSuccess)                      \
+            return hip_fail((h), e_, what);        \
+    } while (0)
+
+void plan_workspace(tbe_s* h)
+{
+    const int64_t nmax = h->max_indices;
+    const int64_t bags = (int64_t)h->T * h->max_batch;
+    (void)bags;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    h->off_meta = take(sizeof(TableMeta) * (size_t)h->T);
+    h->off_rowbase = take(sizeof(uint32_t) * (size_t)(h->T + 1));
+    h->off_counters = take(sizeof(Counters));
+    const size_t nelem = (size_t)nmax + 64;  // +1 for seg_offsets' sentinel, rounded
+    for (int i = 0; i < 2; ++i) {
+        h->off_keys[i] = take(4 * nelem);
+        h->off_vals[i] = take(4 * nelem);
+    }
+    const int64_t sort_tiles = std::max<int64_t>(1, ceil_div(nmax, kSortTile));
+    const int64_t hist_len = 256 * sort_tiles;
+    h->off_hist = take(4 * (size_t)hist_len);
+    const int64_t rl_tiles = std::max<int64_t>(1, ceil_div(nmax, kRlTile));
+    const int64_t scan_blocks = std::max(ceil_div(hist_len, kScanTile), ceil_div(rl_tiles, kScanTile));
+    h->off_scan_tmp = take(4 * (size_t)(scan_blocks + 1));
+    h->off_rl_counts = take(4 * (size_t)(rl_tiles + 16));
+    const int64_t chunks = std::max<int64_t>(1, ceil_div(nmax, kChunk));
+    h->off_chunk_first = take(4 * (size_t)(chunks + 1));
+    const int dpad = (int)align_up((size_t)h->dmax, 4);
+    h->off_partials = take(4 * (size_t)chunks * 2 * (size_t)dpad);
+    h->off_long_list = take(4 * (size_t)(nmax / kLongRun + 2));
+    h->workspace_bytes = off;
+}
+
+// exclusive scan of a uint32 device array in place (three launches)
+tbe_status_t device_scan(tbe_s* h, uint32_t* data, int64_t n, int64_t* total_out, hipStream_t st)
+{
+    if (n <= 0)
+        return TBE_OK;
+    const int nb = (int)ceil_div(n, kScanTile);
+    uint32_t* tmp = h->ws<uint32_t>(h->off_scan_tmp);
+    hipLaunchKernelGGL(scan_reduce_kernel, dim3(nb), dim3(kScanThreads), 0, st, data, tmp, n);
+    hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kScanThreads), 0, st, tmp, nb, total_out);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(nb), dim3(kScanThreads), 0, st, data, tmp, n);
+    TBE_LAUNCH_CHECK(h, "device_scan");
+    return TBE_OK;
+}
+
+tbe_status_t check_call(tbe_s* h, const void* d_indices, const void* d_offsets, int64_t num_indices,
+                        int32_t batch)
+{
+    if (!h)
+        return TBE_ERR_INVALID_ARG;
+    if (!h->bound)
+        return TBE_ERR_NOT_BOUND;
+    if (!d_offsets || batch < 0 || batch > h->max_batch || num_indices < 0 ||
+        num_indices > h->max_indices || (num_indices > 0 && !d_indices))
+        return TBE_ERR_INVALID_ARG;
+    return TBE_OK;
+}
+
+template <typename WT>
+tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, int32_t batch, float* out,
+                            hipStream_t st)
+{
+    const int num_bags = h->T * batch;
+    const int per_block = kFwdThreads / kWave;
+    const dim3 grid((unsigned)ceil_div(num_bags, per_block)), block(kFwdThreads);
+    const TableMeta* meta = h->ws<TableMeta>(h->off_meta);
+    const WT* w = static_cast<const WT*>(h->d_weights);
+    const int sumD = (int)h->sumD;
+#define FWD(EPL, KMAX)                                                                              \
+    hipLaunchKernelGGL((forward_kernel<WT, EPL, KMAX>), grid, block, 0, st, meta, w, idx, off, out, \
+                       batch, num_bags, sumD)
+    if constexpr (sizeof(WT) == 4) {
+        if (h->fwd_kmax == 1)
+            FWD(4, 1);
+        else
+            FWD(4, 2);
+    } else {
+        if (h->fwd_epl == 8)
+            FWD(8, 1);
+        else if (h->fwd_kmax == 1)
+            FWD(4, 1);
+        else
+            FWD(4, 2);
+    }
+#undef FWD
+    TBE_LAUNCH_CHECK(h, "forward_kernel");
+    return TBE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tbe_status_string(tbe_status_t s)
+{
+    switch (s) {
+        case TBE_OK: return "ok";
+        case TBE_ERR_INVALID_ARG: return "invalid argument";
+        case TBE_ERR_UNSUPPORTED: return "unsupported configuration";
+        case TBE_ERR_NOT_BOUND: return "device buffers not bound";
+        case TBE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case TBE_ERR_INDEX_OUT_OF_RANGE: return "index out of range";
+        case TBE_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* tbe_last_hip_error(tbe_handle_t h) { return h ? h->last_hip_error.c_str() : ""; }
+
+tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
+{
+    if (!cfg || !out_handle || !cfg->rows || !cfg->dims || cfg->num_tables < 1 || cfg->max_batch < 0 ||
+        cfg->max_indices < 0)
+        return TBE_ERR_INVALID_ARG;
+    for (int t = 0; t < cfg->num_tables; ++t)
+        if (cfg->rows[t] <= 0 || cfg->dims[t] <= 0)
+            return TBE_ERR_INVALID_ARG;
+    if ((cfg->weight_dtype != TBE_DTYPE_FP32 && cfg->weight_dtype != TBE_DTYPE_FP16) ||
+        cfg->pooling != TBE_POOLING_SUM)
+        return TBE_ERR_UNSUPPORTED;
+    if (cfg->max_indices >= ((int64_t)1 << 31) - ((int64_t)1 << 24) ||
+        (int64_t)cfg->num_tables * cfg->max_batch >= ((int64_t)1 << 31) - 1024)
+        return TBE_ERR_UNSUPPORTED;
+    int64_t total_rows = 0, sumD = 0;
+    bool all8 = true;
+    int dmax = 0;
+    for (int t = 0; t < cfg->num_tables; ++t) {
+        if (cfg->dims[t] % 4 != 0 || cfg->dims[t] > kMaxDim)
+            return TBE_ERR_UNSUPPORTED;
+        total_rows += cfg->rows[t];
+        if (total_rows >= ((int64_t)1 << 32) - 1)
+            return TBE_ERR_UNSUPPORTED;
+        sumD += cfg->dims[t];
+        all8 = all8 && cfg->dims[t] % 8 == 0;
+        dmax = std::max(dmax, cfg->dims[t]);
+    }
+    if (sumD >= ((int64_t)1 << 31))
+        return TBE_ERR_UNSUPPORTED;
+
+    tbe_s* h = new (std::nothrow) tbe_s();
+    if (!h)
+        return TBE_ERR_INVALID_ARG;
+    h->T = cfg->num_tables;
+    h->rows.assign(cfg->rows, cfg->rows + h->T);
+    h->dims.assign(cfg->dims, cfg->dims + h->T);
+    h->dtype = cfg->weight_dtype;
+    h->max_batch = cfg->max_batch;
+    h->max_indices = cfg->max_indices;
+    h->sumD = sumD;
+    h->dmax = dmax;
+    h->fwd_epl = (h->dtype == TBE_DTYPE_FP16 && all8) ? 8 : 4;
+    h->fwd_kmax = (int)ceil_div(dmax, h->fwd_epl * kWave);
+    h->key_bits = 1;
+    while (h->key_bits < 32 && ((int64_t)1 << h->key_bits) < total_rows)
+        ++h->key_bits;
+
+    h->woff.resize(h->T + 1);
+    h->soff.resize(h->T + 1);
+    h->coloff.resize(h->T + 1);
+    h->meta.resize(h->T);
+    int64_t w = 0, s = 0;
+    int32_t c = 0;
+    for (int t = 0; t < h->T; ++t) {
+        h->woff[t] = w;
+        h->soff[t] = s;
+        h->coloff[t] = c;
+        TableMeta& m = h->meta[t];
+        m.woff = w;
+        m.rbase = (uint32_t)s;
+        m.dim = h->dims[t];
+        m.col = c;
+        m.lpr_fwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], h->fwd_epl)));
+        m.lpr_bwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], 4)));
+        m.pad = 0;
+        w += h->rows[t] * (int64_t)h->dims[t];
+        s += h->rows[t];
+        c += h->dims[t];
+    }
+    h->woff[h->T] = w;
+    h->soff[h->T] = s;
+    h->coloff[h->T] = c;
+    h->weight_bytes = (size_t)w * (h->dtype == TBE_DTYPE_FP32 ? 4 : 2);
+    h->state_bytes = (size_t)s * 4;
+    plan_workspace(h);
+    *out_handle = h;
+    return TBE_OK;
+}
+
+tbe_status_t tbe_destroy(tbe_handle_t h)
+{
+    if (!h)
+        return TBE_OK;
+    for (hipEvent_t e : h->ev_pool)
+        (void)hipEventDestroy(e);
+    delete h;
+    return TBE_OK;
+}
+
+tbe_status_t tbe_query_sizes(tbe_handle_t h, size_t* weight_bytes, size_t* state_bytes,
+                             size_t* workspace_bytes, int64_t* weight_offsets, int64_t* state_offsets,
+                             int32_t* out_col_offsets)
+{
+    if (!h)
+        return TBE_ERR_INVALID_ARG;
+    if (weight_bytes)
+        *weight_bytes = h->weight_bytes;
+    if (state_bytes)
+        *state_bytes = h->state_bytes;
+    if (workspace_bytes)
+        *workspace_bytes = h->workspace_bytes;
+    if (weight_offsets)
+        std::memcpy(weight_offsets, h->woff.data(), sizeof(int64_t) * (h->T + 1));
+    if (state_offsets)
+        std::memcpy(state_offsets, h->soff.data(), sizeof(int64_t) * (h->T + 1));
+    if (out_col_offsets)
+        std::memcpy(out_col_offsets, h->coloff.data(), sizeof(int32_t) * (h->T + 1));
+    return TBE_OK;
+}
+
+tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_workspace,
+                      size_t workspace_bytes)
+{
+    if (!h || !d_weights || !d_state || !d_workspace)
+        return TBE_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_workspace) & 255) || (reinterpret_cast<uintptr_t>(d_weights) & 15) ||
+        (reinterpret_cast<uintptr_t>(d_state) & 3))
+        return TBE_ERR_INVALID_ARG;
+    if (workspace_bytes < h->workspace_bytes)
+        return TBE_ERR_WORKSPACE_TOO_SMALL;
+    h->bound = false;
+    h->d_weights = d_weights;
+    h->d_state = d_state;
+    h->d_ws = static_cast<char*>(d_workspace);
+    std::vector<uint32_t> rb(h->T + 1);
+    for (int t = 0; t <= h->T; ++t)
+        rb[t] = (uint32_t)h->soff[t];
+    Counters zero;
+    std::memset(&zero, 0, sizeof(zero));
+    TBE_HIP_CHECK(h, hipMemcpy(h->d_ws + h->off_meta, h->meta.data(), sizeof(TableMeta) * h->T,
+                               hipMemcpyHostToDevice));
+    TBE_HIP_CHECK(h, hipMemcpy(h->d_ws + h->off_rowbase, rb.data(), sizeof(uint32_t) * (h->T + 1),
+                               hipMemcpyHostToDevice));
+    TBE_HIP_CHECK(h, hipMemcpy(h->d_ws + h->off_counters, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    h->bound = true;
+    h->final_buf = -1;
+    return TBE_OK;
+}
+
+tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                         int64_t num_indices, int32_t batch, float* d_out, void* stream)
+{
+    tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
+    if (rc != TBE_OK)
+        return rc;
+    if (batch == 0)
+        return TBE_OK;
+    if (!d_out)
+        return TBE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTimer tm(h, SLOT_FORWARD, st);
+    if (h->dtype == TBE_DTYPE_FP32)
+        return launch_forward<float>(h, d_indices, d_offsets, batch, d_out, st);
+    return launch_forward<__half>(h, d_indices, d_offsets, batch, d_out, st);
+}
+
+tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
+                                          const int64_t* d_offsets, int64_t num_indices, int32_t batch,
+                                          const float* d_grad_out, float lr, float eps, void* stream)
+{
+    tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
+    if (rc != TBE_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Counters* counters = h->ws<Counters>(h->off_counters);
+    const int32_t n = (int32_t)num_indices;
+    if (batch == 0 || n == 0) {
+        hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(1), 0, st, counters);
+        TBE_LAUNCH_CHECK(h, "clear_counters_kernel");
+        h->final_buf = 0;
+        return TBE_OK;
+    }
+    if (!d_grad_out)
+        return TBE_ERR_INVALID_ARG;
+
+    const int num_bags = h->T * batch;
+    const uint32_t* row_base = h->ws<uint32_t>(h->off_rowbase);
+    uint32_t* keys[2] = {h->ws<uint32_t>(h->off_keys[0]), h->ws<uint32_t>(h->off_keys[1])};
+    int32_t* vals[2] = {h->ws<int32_t>(h->off_vals[0]), h->ws<int32_t>(h->off_vals[1])};
+
+    {   // a2: (table,row) keys and bag payloads
+        ScopedTimer tm(h, SLOT_BUILD_KEYS, st);
+        hipLaunchKernelGGL(build_keys_kernel, dim3((unsigned)ceil_div(num_bags, kKeyBags)), dim3(256), 0, st,
+                           row_base, d_indices, d_offsets, keys[0], vals[0], batch, num_bags, counters);
+        TBE_LAUNCH_CHECK(h, "build_keys_kernel");
+    }
+
+    // a3: stable LSD radix sort over only the significant key bits
+    const int passes = (int)ceil_div(h->key_bits, 8);
+    const int num_tiles = (int)ceil_div(n, kSortTile);
+    uint32_t* hist = h->ws<uint32_t>(h->off_hist);
+    int cur = 0, shift = 0;
+    for (int p = 0; p < passes; ++p) {
+        const int bits = h->key_bits / passes + (p < h->key_bits % passes ? 1 : 0);
+        {
+            ScopedTimer tm(h, SLOT_RADIX_HIST, st);
+            hipLaunchKernelGGL(radix_hist_kernel, dim3(num_tiles), dim3(kSortThreads), 0, st, keys[cur], hist,
+                               n, num_tiles, shift, bits);
+            TBE_LAUNCH_CHECK(h, "radix_hist_kernel");
+        }
+        {
+            ScopedTimer tm(h, SLOT_RADIX_SCAN, st);
+            rc = device_scan(h, hist, (int64_t)num_tiles << bits, nullptr, st);
+            if (rc != TBE_OK)
+                return rc;
+        }
+        {
+            ScopedTimer tm(h, SLOT_RADIX_SCATTER, st);
+            hipLaunchKernelGGL(radix_scatter_kernel, dim3(num_tiles), dim3(kSortThreads), 0, st, keys[cur],
+                               vals[cur], keys[cur ^ 1], vals[cur ^ 1], hist, n, num_tiles, shift, bits);
+            TBE_LAUNCH_CHECK(h, "radix_scatter_kernel");
+        }
+        cur ^= 1;
+        shift += bits;
+    }
+    h->final_buf = cur;
+
+    // a4: run heads -> unique keys, segment offsets, per-chunk first run (the free ping-pong pair
+    // of the sort holds unique_keys / seg_offsets)
+    uint32_t* unique_keys = keys[cur ^ 1];
+    int32_t* seg_offsets = vals[cur ^ 1];
+    int32_t* chunk_first = h->ws<int32_t>(h->off_chunk_first);
+    const int num_chunks = (int)ceil_div(n, kChunk);
+    {
+        ScopedTimer tm(h, SLOT_RUNLENGTH, st);
+        const int rl_tiles = (int)ceil_div(n, kRlTile);
+        uint32_t* rl_counts = h->ws<uint32_t>(h->off_rl_counts);
+        hipLaunchKernelGGL(runlength_count_kernel, dim3(rl_tiles), dim3(kRlThreads), 0, st, keys[cur],
+                           rl_counts, n);
+        rc = device_scan(h, rl_counts, rl_tiles, nullptr, st);
+        if (rc != TBE_OK)
+            return rc;
+        hipLaunchKernelGGL(runlength_write_kernel, dim3(rl_tiles), dim3(kRlThreads), 0, st, keys[cur],
+                           rl_counts, unique_keys, seg_offsets, chunk_first, counters, n, num_chunks);
+        TBE_LAUNCH_CHECK(h, "runlength kernels");
+    }
+
+    // a5 + a6: on-chip aggregation per run, one AdaGrad step per touched row
+    BwdArgs a;
+    a.meta = h->ws<TableMeta>(h->off_meta);
+    a.row_base = row_base;
+    a.sorted_keys = keys[cur];
+    a.sorted_vals = vals[cur];
+    a.unique_keys = unique_keys;
+    a.seg_offsets = seg_offsets;
+    a.chunk_first_run = chunk_first;
+    a.counters = counters;
+    a.grad_out = d_grad_out;
+    a.weights = h->d_weights;
+    a.moments = h->d_state;
+    a.partials = h->ws<float>(h->off_partials);
+    a.long_list = h->ws<uint32_t>(h->off_long_list);
+    a.n = n;
+    a.num_chunks = num_chunks;
+    a.T = h->T;
+    a.sumD = (int32_t)h->sumD;
+    a.dpad = (int32_t)align_up((size_t)h->dmax, 4);
+    a.lr = lr;
+    a.eps = eps;
+    const int per_block = kBwdThreads / kWave;
+    {
+        ScopedTimer tm(h, SLOT_REDUCE_UPDATE, st);
+        const dim3 grid((unsigned)ceil_div(num_chunks, per_block)), block(kBwdThreads);
+        if (h->dtype == TBE_DTYPE_FP32)
+            hipLaunchKernelGGL(reduce_update_kernel<float>, grid, block, 0, st, a);
+        else
+            hipLaunchKernelGGL(reduce_update_kernel<__half>, grid, block, 0, st, a);
+        TBE_LAUNCH_CHECK(h, "reduce_update_kernel");
+    }
+    {
+        ScopedTimer tm(h, SLOT_LONG_FIXUP, st);
+        const int64_t max_long = n / kLongRun + 1;
+        const dim3 grid((unsigned)std::min<int64_t>(2048, ceil_div(max_long, per_block))), block(kBwdThreads);
+        if (h->dtype == TBE_DTYPE_FP32)
+            hipLaunchKernelGGL(long_run_fixup_kernel<float>, grid, block, 0, st, a);
+        else
+            hipLaunchKernelGGL(long_run_fixup_kernel<__half>, grid, block, 0, st, a);
+        TBE_LAUNCH_CHECK(h, "long_run_fixup_kernel");
+    }
+    return TBE_OK;
+}
+
+tbe_status_t tbe_backward_artifacts(tbe_handle_t h, const uint32_t** d_sorted_keys,
+                                    const int32_t** d_sorted_vals, const uint32_t** d_unique_keys,
+                                    const int32_t** d_seg_offsets, const int64_t** d_num_unique)
+{
+    if (!h)
+        return TBE_ERR_INVALID_ARG;
+    if (!h->bound)
+        return TBE_ERR_NOT_BOUND;
+    if (h->final_buf < 0)
+        return TBE_ERR_INVALID_ARG;
+    const int cur = h->final_buf;
+    if (d_sorted_keys)
+        *d_sorted_keys = h->ws<uint32_t>(h->off_keys[cur]);
+    if (d_sorted_vals)
+        *d_sorted_vals = h->ws<int32_t>(h->off_vals[cur]);
+    if (d_unique_keys)
+        *d_unique_keys = h->ws<uint32_t>(h->off_keys[cur ^ 1]);
+    if (d_seg_offsets)
+        *d_seg_offsets = h->ws<int32_t>(h->off_vals[cur ^ 1]);
+    if (d_num_unique)
+        *d_num_unique = &h->ws<Counters>(h->off_counters)->num_unique;
+    return TBE_OK;
+}
+
+tbe_status_t tbe_check_inputs(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                              int64_t num_indices, int32_t batch, void* stream)
+{
+    tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
+    if (rc != TBE_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Counters* counters = h->ws<Counters>(h->off_counters);
+    const int num_bags = h->T * batch;
+    Counters host;
+    std::memset(&host, 0, sizeof(host));
+    if (num_bags == 0)
+        return num_indices == 0 ? TBE_OK : TBE_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(1), 0, st, counters);
+    hipLaunchKernelGGL(check_inputs_kernel, dim3((unsigned)ceil_div(num_bags, 256)), dim3(256), 0, st,
+                       h->ws<TableMeta>(h->off_meta), h->ws<uint32_t>(h->off_rowbase), d_indices, d_offsets,
+                       num_indices, batch, num_bags, counters);
+    TBE_LAUNCH_CHECK(h, "check_inputs_kernel");
+    TBE_HIP_CHECK(h, hipMemcpyAsync(&host, counters, sizeof(host), hipMemcpyDeviceToHost, st));
+    TBE_HIP_CHECK(h, hipStreamSynchronize(st));
+    if (host.check_flags & 1u)
+        return TBE_ERR_INVALID_ARG;
+    if (host.check_flags & 2u)
+        return TBE_ERR_INDEX_OUT_OF_RANGE;
+    return TBE_OK;
+}
+
+tbe_status_t tbe_profile_enable(tbe_handle_t h, int32_t max_calls)
+{
+    if (!h || max_calls < 0)
+        return TBE_ERR_INVALID_ARG;
+    for (hipEvent_t e : h->ev_pool)
+        (void)hipEventDestroy(e);
+    h->ev_pool.clear();
+    h->recs.clear();
+    h->ev_used = 0;
+    h->profiling = false;
+    if (max_calls == 0)
+        return TBE_OK;
+    const size_t want = (size_t)max_calls * 2 * 24;  // <= 24 timed kernel groups per call
+    h->ev_pool.reserve(want);
+    for (size_t i = 0; i < want; ++i) {
+        hipEvent_t e;
+        TBE_HIP_CHECK(h, hipEventCreate(&e));
+        h->ev_pool.push_back(e);
+    }
+    h->recs.reserve(want / 2);
+    h->profiling = true;
+    return TBE_OK;
+}
+
+tbe_status_t tbe_profile_read(tbe_handle_t h, int32_t capacity, const char** names, int64_t* launches,
+                              double* total_ms, int32_t* num_slots)
+{
+    if (!h || capacity < SLOT_COUNT || !names || !launches || !total_ms || !num_slots)
+        return TBE_ERR_INVALID_ARG;
+    for (int s = 0; s < SLOT_COUNT; ++s) {
+        names[s] = kSlotNames[s];
+        launches[s] = 0;
+        total_ms[s] = 0.0;
+    }
+    *num_slots = SLOT_COUNT;
+    for (const ProfRec& r : h->recs) {
+        TBE_HIP_CHECK(h, hipEventSynchronize(r.stop));
+        float ms = 0.f;
+        TBE_HIP_CHECK(h, hipEventElapsedTime(&ms, r.start, r.stop));
+        launches[r.slot] += 1;
+        total_ms[r.slot] += ms;
+    }
+    h->recs.clear();
+    h->ev_used = 0;
+    return TBE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,897 @@
+// Device kernels of the table-batched embedding-bag library for gfx950 (CDNA4, wave64).
+//
+// Forward: Section 2 "Embedding operators" + Section 5.1 (all tables in one launch).
+// Backward: Section 5.1 (gradient sorting by rows, on-chip aggregation, fused optimizer) and
+// Section 5.2 (row-wise AdaGrad) of arxiv 2104.05158.
+//
+// Everything on this path is a gather / scan / sort bound by HBM bandwidth: no MFMA.  The lane
+// mapping is the same everywhere: a row of D elements is covered by LPR = pow2ceil(D / EPL) lanes
+// (EPL contiguous elements per lane, vector loads), and the 64 / LPR lane groups of a wavefront
+// fetch different rows at the same time; sums across groups and across a row use xor-shuffles.
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tbe {
+
+constexpr int kWave = 64;
+
+// ---- geometry constants shared by host and device ----
+constexpr int kFwdThreads = 256;          // 4 wavefronts = 4 bags per workgroup
+constexpr int kFwdUnroll = 4;             // row loads in flight per lane group
+constexpr int kKeyBags = 256;             // bags per workgroup in the key build
+constexpr int kSortThreads = 512;         // 8 wavefronts
+constexpr int kSortKeysPerThread = 16;
+constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys staged in LDS
+constexpr int kScanThreads = 256;
+constexpr int kScanPerThread = 16;
+constexpr int kScanTile = kScanThreads * kScanPerThread;      // 4096
+constexpr int kRlThreads = 256;
+constexpr int kRlPerThread = 16;
+constexpr int kRlTile = kRlThreads * kRlPerThread;            // 4096 sorted positions
+constexpr int kChunk = 256;               // sorted positions owned by one wavefront in the update
+constexpr int kLongRun = 512;             // runs longer than this are split over their chunks
+constexpr int kBwdThreads = 256;          // 4 wavefronts = 4 chunks per workgroup
+constexpr int kBwdUnroll = 4;
+constexpr int kMaxDim = 512;
+
+struct TableMeta {      // 32 bytes, one per table, in the workspace head
+    int64_t woff;       // first element of the table in the flat weight array
+    uint32_t rbase;     // linear id of the table's row 0
+    int32_t dim;        // D_t
+    int32_t col;        // first output column
+    int32_t lpr_fwd;    // log2 lanes per row, forward (EPL elements per lane)
+    int32_t lpr_bwd;    // log2 lanes per row, backward (4 floats per lane)
+    int32_t pad;
+};
+
+struct Counters {       // workspace scalars
+    int64_t num_unique;
+    uint32_t long_count;
+    uint32_t check_flags;
+    uint32_t pad[4];
+};
+
+// ---------------------------------------------------------------- small helpers
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <typename WT, int EPL>
+struct RowIO;
+
+template <>
+struct RowIO<float, 4> {
+    __device__ static __forceinline__ void load(const float* p, float (&f)[4])
+    {
+        float4 v = *reinterpret_cast<const float4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    __device__ static __forceinline__ void store(float* p, const float (&f)[4])
+    {
+        *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+    }
+};
+
+template <>
+struct RowIO<__half, 4> {
+    __device__ static __forceinline__ void load(const __half* p, float (&f)[4])
+    {
+        uint2 v = *reinterpret_cast<const uint2*>(p);
+        float2 a = __half22float2(*reinterpret_cast<__half2*>(&v.x));
+        float2 b = __half22float2(*reinterpret_cast<__half2*>(&v.y));
+        f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
+    }
+    __device__ static __forceinline__ void store(__half* p, const float (&f)[4])
+    {
+        uint2 v;
+        *reinterpret_cast<__half2*>(&v.x) = __floats2half2_rn(f[0], f[1]);
+        *reinterpret_cast<__half2*>(&v.y) = __floats2half2_rn(f[2], f[3]);
+        *reinterpret_cast<uint2*>(p) = v;
+    }
+};
+
+template <>
+struct RowIO<__half, 8> {
+    __device__ static __forceinline__ void load(const __half* p, float (&f)[8])
+    {
+        uint4 v = *reinterpret_cast<const uint4*>(p);
+        float2 a = __half22float2(*reinterpret_cast<__half2*>(&v.x));
+        float2 b = __half22float2(*reinterpret_cast<__half2*>(&v.y));
+        float2 c = __half22float2(*reinterpret_cast<__half2*>(&v.z));
+        float2 d = __half22float2(*reinterpret_cast<__half2*>(&v.w));
+        f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
+        f[4] = c.x; f[5] = c.y; f[6] = d.x; f[7] = d.y;
+    }
+};
+
+// ---------------------------------------------------------------- forward (Section 2, Section 5.1)
+//
+// One wavefront per bag.  The bag's indices are read 64 at a time, coalesced, and handed to the
+// lane groups by shuffle; each group streams whole rows with EPL-element vector loads, kFwdUnroll
+// rows in flight, accumulating in fp32 registers.  The groups' partial sums meet in an xor
+// butterfly and group 0 writes the D_t pooled values with one coalesced store.
+template <typename WT, int EPL, int KMAX>
+__global__ __launch_bounds__(kFwdThreads) void forward_kernel(
+    const TableMeta* __restrict__ meta, const WT* __restrict__ weights,
+    const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+    float* __restrict__ out, int32_t B, int32_t num_bags, int32_t sumD)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int j = uniform(blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6));
+    if (j >= num_bags)
+        return;
+    const int t = j / B;
+    const int b = j - t * B;
+    const TableMeta m = meta[t];
+    const int D = m.dim;
+    const int lprl = m.lpr_fwd;
+    const int LPR = 1 << lprl;
+    const int G = kWave >> lprl;
+    const int sub = lane & (LPR - 1);
+    const int grp = lane >> lprl;
+    const WT* __restrict__ wbase = weights + m.woff;
+
+    const int64_t start = offsets[j];
+    const int L = (int)(offsets[j + 1] - start);
+
+    float acc[KMAX][EPL];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+            acc[k][e] = 0.f;
+
+    for (int base = 0; base < L; base += kWave) {
+        const int n = min(kWave, L - base);
+        const int my = lane < n ? indices[start + base + lane] : 0;
+        for (int i0 = 0; i0 < n; i0 += G * kFwdUnroll) {
+            float v[kFwdUnroll][KMAX][EPL];
+#pragma unroll
+            for (int u = 0; u < kFwdUnroll; ++u) {
+                const int i = i0 + u * G + grp;
+                const int idx = __shfl(my, i & (kWave - 1));
+                const bool ok = i < n;
+                const WT* rp = wbase + (int64_t)idx * D;
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k) {
+                    const int e0 = (sub + k * LPR) * EPL;
+                    if (ok && e0 < D) {
+                        RowIO<WT, EPL>::load(rp + e0, v[u][k]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e)
+                            v[u][k][e] = 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kFwdUnroll; ++u)
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e)
+                        acc[k][e] += v[u][k][e];
+        }
+    }
+
+    for (int s = LPR; s < kWave; s <<= 1) {
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                acc[k][e] += __shfl_xor(acc[k][e], s);
+    }
+
+    if (grp == 0) {
+        float* op = out + (int64_t)b * sumD + m.col;
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const int e0 = (sub + k * LPR) * EPL;
+            if (e0 < D) {
+#pragma unroll
+                for (int q = 0; q < EPL; q += 4)
+                    *reinterpret_cast<float4*>(op + e0 + q) =
+                        make_float4(acc[k][q], acc[k][q + 1], acc[k][q + 2], acc[k][q + 3]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- key build (Section 5.1, "sorting by rows")
+//
+// key[p] = rbase_t + indices[p] (the row's linear id over all tables), val[p] = b, for every lookup
+// position p.  A workgroup takes kKeyBags consecutive bags, keeps their offsets in LDS and walks the
+// positions they cover with coalesced loads/stores; the bag of a position is found by bisection in LDS.
+__global__ __launch_bounds__(256) void build_keys_kernel(
+    const uint32_t* __restrict__ row_base, const int32_t* __restrict__ indices,
+    const int64_t* __restrict__ offsets, uint32_t* __restrict__ keys, int32_t* __restrict__ vals,
+    int32_t B, int32_t num_bags, Counters* __restrict__ counters)
+{
+    __shared__ int32_t soff[kKeyBags + 1];
+    const int j0 = blockIdx.x * kKeyBags;
+    const int nb = min(kKeyBags, num_bags - j0);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        counters->num_unique = 0;
+        counters->long_count = 0;
+    }
+    for (int i = threadIdx.x; i <= nb; i += 256)
+        soff[i] = (int32_t)offsets[j0 + i];
+    __syncthreads();
+    const int lo = soff[0], hi = soff[nb];
+    for (int p = lo + threadIdx.x; p < hi; p += 256) {
+        int a = 0, c = nb;  // soff[a] <= p < soff[c]
+        while (c - a > 1) {
+            const int mid = (a + c) >> 1;
+            if (soff[mid] <= p)
+                a = mid;
+            else
+                c = mid;
+        }
+        const int j = j0 + a;
+        const int t = j / B;
+        keys[p] = row_base[t] + (uint32_t)indices[p];
+        vals[p] = j - t * B;
+    }
+}
+
+// ---------------------------------------------------------------- LSD radix sort (stable), LDS-staged
+//
+// Per pass: (1) per-tile digit histogram, (2) exclusive scan of the digit-major histogram table,
+// (3) scatter: every wavefront ranks its 16 x 64 keys with ballot-based digit matching into per-wave
+// LDS counters, the tile is reordered by digit inside LDS and then written out in runs that are
+// contiguous in global memory.  Order inside a tile is (wavefront, round, lane) = ascending position,
+// so equal digits keep their input order and the whole sort is stable.
+
+__device__ __forceinline__ uint64_t match_digit(uint32_t dg, bool valid, int bits)
+{
+    uint64_t peers = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+        const bool bit = (dg >> b) & 1u;
+        const uint64_t bal = __ballot(bit);
+        peers &= bit ? bal : ~bal;
+    }
+    return peers;
+}
+
+__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
+    const uint32_t* __restrict__ keys, uint32_t* __restrict__ hist, int32_t n, int32_t num_tiles,
+    int shift, int bits)
+{
+    __shared__ uint32_t s_hist[kSortThreads / kWave][256];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int nd = 1 << bits;
+    const uint32_t mask = nd - 1;
+    for (int i = threadIdx.x; i < (kSortThreads / kWave) * 256; i += kSortThreads)
+        (&s_hist[0][0])[i] = 0;
+    __syncthreads();
+    volatile uint32_t* wh = s_hist[wave];
+    const int base = blockIdx.x * kSortTile + wave * (kSortTile / (kSortThreads / kWave));
+    const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll 4
+    for (int r = 0; r < kSortKeysPerThread; ++r) {
+        const int q = base + r * kWave + lane;
+        const bool valid = q < n;
+        const uint32_t dg = valid ? ((keys[q] >> shift) & mask) : 0u;
+        const uint64_t peers = match_digit(dg, valid, bits);
+        if (valid && (peers & lt) == 0)
+            wh[dg] = wh[dg] + (uint32_t)__popcll(peers);
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < nd; d += kSortThreads) {
+        uint32_t s = 0;
+#pragma unroll
+        for (int w = 0; w < kSortThreads / kWave; ++w)
+            s += s_hist[w][d];
+        hist[(int64_t)d * num_tiles + blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
+    const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
+    uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
+    const uint32_t* __restrict__ hist_scanned, int32_t n, int32_t num_tiles, int shift, int bits)
+{
+    constexpr int kWaves = kSortThreads / kWave;
+    __shared__ uint32_t s_keys[kSortTile];
+    __shared__ int32_t s_vals[kSortTile];
+    __shared__ uint32_t s_whist[kWaves][256];
+    __shared__ uint32_t s_dstart[256];
+    __shared__ uint32_t s_goff[256];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int nd = 1 << bits;
+    const uint32_t mask = nd - 1;
+    const int tile = blockIdx.x;
+    const int tile_base = tile * kSortTile;
+    const int tile_cnt = min(kSortTile, n - tile_base);
+
+    for (int i = threadIdx.x; i < kWaves * 256; i += kSortThreads)
+        (&s_whist[0][0])[i] = 0;
+    __syncthreads();
+
+    uint32_t key[kSortKeysPerThread];
+    int32_t val[kSortKeysPerThread];
+    uint32_t rank[kSortKeysPerThread];
+    const int base = tile_base + wave * (kSortTile / kWaves);
+#pragma unroll
+    for (int r = 0; r < kSortKeysPerThread; ++r) {
+        const int q = base + r * kWave + lane;
+        const bool valid = q < n;
+        key[r] = valid ? keys_in[q] : 0xffffffffu;
+        val[r] = valid ? vals_in[q] : 0;
+    }
+    volatile uint32_t* wh = s_whist[wave];
+    const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < kSortKeysPerThread; ++r) {
+        const int q = base + r * kWave + lane;
+        const bool valid = q < n;
+        const uint32_t dg = (key[r] >> shift) & mask;
+        const uint64_t peers = match_digit(dg, valid, bits);
+        const uint32_t pre = valid ? wh[dg] : 0u;
+        const uint32_t below = (uint32_t)__popcll(peers & lt);
+        if (valid && below == 0)
+            wh[dg] = pre + (uint32_t)__popcll(peers);
+        rank[r] = pre + below;
+    }
+    __syncthreads();
+
+    // per digit: exclusive prefix over the wavefronts, and the tile total
+    if ((int)threadIdx.x < nd) {
+        uint32_t run = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const uint32_t c = s_whist[w][threadIdx.x];
+            s_whist[w][threadIdx.x] = run;
+            run += c;
+        }
+        s_dstart[threadIdx.x] = run;
+    }
+    __syncthreads();
+    // exclusive scan of the (up to 256) digit totals by wavefront 0: 4 digits per lane
+    if (wave == 0) {
+        uint32_t c[4];
+        uint32_t s = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int d = lane * 4 + i;
+            c[i] = d < nd ? s_dstart[d] : 0u;
+            s += c[i];
+        }
+        uint32_t incl = s;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o);
+            if (lane >= o)
+                incl += up;
+        }
+        uint32_t ex = incl - s;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int d = lane * 4 + i;
+            if (d < nd) {
+                s_dstart[d] = ex;
+                s_goff[d] = hist_scanned[(int64_t)d * num_tiles + tile] - ex;
+            }
+            ex += c[i];
+        }
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int r = 0; r < kSortKeysPerThread; ++r) {
+        const int q = base + r * kWave + lane;
+        if (q < n) {
+            const uint32_t dg = (key[r] >> shift) & mask;
+            const uint32_t pos = s_dstart[dg] + s_whist[wave][dg] + rank[r];
+            s_keys[pos] = key[r];
+            s_vals[pos] = val[r];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortKeysPerThread; ++i) {
+        const int p = threadIdx.x + i * kSortThreads;
+        if (p < tile_cnt) {
+            const uint32_t k = s_keys[p];
+            const uint32_t g = s_goff[(k >> shift) & mask] + (uint32_t)p;
+            keys_out[g] = k;
+            vals_out[g] = s_vals[p];
+        }
+    }
+}
+
+// ---------------------------------------------------------------- device-wide exclusive scan (uint32)
+
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* s_wave /*[4]*/,
+                                                             uint32_t& block_total)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o)
+            incl += up;
+    }
+    if (lane == kWave - 1)
+        s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t woff = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t c = s_wave[w];
+        if (w < wave)
+            woff += c;
+        tot += c;
+    }
+    block_total = tot;
+    __syncthreads();
+    return woff + incl - v;
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_reduce_kernel(
+    const uint32_t* __restrict__ data, uint32_t* __restrict__ block_sums, int64_t n)
+{
+    __shared__ uint32_t s_wave[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    uint32_t s = 0;
+    if (base + kScanPerThread <= n) {
+        const uint4* p = reinterpret_cast<const uint4*>(data + base);
+#pragma unroll
+        for (int i = 0; i < kScanPerThread / 4; ++i) {
+            const uint4 v = p[i];
+            s += v.x + v.y + v.z + v.w;
+        }
+    } else {
+        for (int i = 0; i < kScanPerThread; ++i)
+            if (base + i < n)
+                s += data[base + i];
+    }
+    uint32_t tot;
+    (void)block_exclusive_scan_256(s, s_wave, tot);
+    if (threadIdx.x == 0)
+        block_sums[blockIdx.x] = tot;
+}
+
+// single workgroup: exclusive scan of block_sums[nb] in place; optional total (as int64) to *total_out
+__global__ __launch_bounds__(kScanThreads) void scan_top_kernel(uint32_t* __restrict__ block_sums,
+                                                                int32_t nb, int64_t* total_out)
+{
+    __shared__ uint32_t s_wave[4];
+    uint32_t carry = 0;
+    for (int base = 0; base < nb; base += kScanThreads) {
+        const int i = base + threadIdx.x;
+        const uint32_t v = i < nb ? block_sums[i] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_exclusive_scan_256(v, s_wave, tot);
+        if (i < nb)
+            block_sums[i] = carry + ex;
+        carry += tot;
+    }
+    if (total_out && threadIdx.x == 0)
+        *total_out = (int64_t)carry;
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(
+    uint32_t* __restrict__ data, const uint32_t* __restrict__ block_sums, int64_t n)
+{
+    __shared__ uint32_t s_wave[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanPerThread;
+    uint32_t v[kScanPerThread];
+    const bool full = base + kScanPerThread <= n;
+    if (full) {
+        const uint4* p = reinterpret_cast<const uint4*>(data + base);
+#pragma unroll
+        for (int i = 0; i < kScanPerThread / 4; ++i) {
+            const uint4 x = p[i];
+            v[4 * i] = x.x; v[4 * i + 1] = x.y; v[4 * i + 2] = x.z; v[4 * i + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kScanPerThread; ++i)
+            v[i] = base + i < n ? data[base + i] : 0u;
+    }
+    uint32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; ++i)
+        s += v[i];
+    uint32_t tot;
+    uint32_t run = block_exclusive_scan_256(s, s_wave, tot) + block_sums[blockIdx.x];
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; ++i) {
+        const uint32_t c = v[i];
+        v[i] = run;
+        run += c;
+    }
+    if (full) {
+        uint4* p = reinterpret_cast<uint4*>(data + base);
+#pragma unroll
+        for (int i = 0; i < kScanPerThread / 4; ++i)
+            p[i] = make_uint4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < kScanPerThread; ++i)
+            if (base + i < n)
+                data[base + i] = v[i];
+    }
+}
+
+// ---------------------------------------------------------------- run-length segmentation (Section 5.1)
+//
+// A sorted position q is a run head when q == 0 or key[q] != key[q-1].  Pass 1 counts heads per
+// tile, a scan turns the counts into the index of each tile's first run, pass 2 writes
+// unique_keys / seg_offsets and, for every kChunk-aligned position, the number of heads before it.
+
+__device__ __forceinline__ void rl_load(const uint32_t* __restrict__ keys, int32_t n, int base,
+                                        uint32_t (&k)[kRlPerThread], uint32_t& prev)
+{
+    if (base + kRlPerThread <= n) {
+        const uint4* p = reinterpret_cast<const uint4*>(keys + base);
+#pragma unroll
+        for (int i = 0; i < kRlPerThread / 4; ++i) {
+            const uint4 x = p[i];
+            k[4 * i] = x.x; k[4 * i + 1] = x.y; k[4 * i + 2] = x.z; k[4 * i + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kRlPerThread; ++i)
+            k[i] = base + i < n ? keys[base + i] : 0u;
+    }
+    prev = (base > 0 && base < n) ? keys[base - 1] : 0u;
+}
+
+__global__ __launch_bounds__(kRlThreads) void runlength_count_kernel(
+    const uint32_t* __restrict__ keys, uint32_t* __restrict__ tile_heads, int32_t n)
+{
+    __shared__ uint32_t s_wave[4];
+    const int base = blockIdx.x * kRlTile + threadIdx.x * kRlPerThread;
+    uint32_t k[kRlPerThread], prev;
+    rl_load(keys, n, base, k, prev);
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < kRlPerThread; ++i) {
+        const int q = base + i;
+        const bool head = q < n && (q == 0 || k[i] != (i == 0 ? prev : k[i - 1]));
+        c += head ? 1u : 0u;
+    }
+    uint32_t tot;
+    (void)block_exclusive_scan_256(c, s_wave, tot);
+    if (threadIdx.x == 0)
+        tile_heads[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(kRlThreads) void runlength_write_kernel(
+    const uint32_t* __restrict__ keys, const uint32_t* __restrict__ tile_first_run,
+    uint32_t* __restrict__ unique_keys, int32_t* __restrict__ seg_offsets,
+    int32_t* __restrict__ chunk_first_run, Counters* __restrict__ counters, int32_t n,
+    int32_t num_chunks)
+{
+    __shared__ uint32_t s_wave[4];
+    const int base = blockIdx.x * kRlTile + threadIdx.x * kRlPerThread;
+    uint32_t k[kRlPerThread], prev;
+    rl_load(keys, n, base, k, prev);
+    bool head[kRlPerThread];
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < kRlPerThread; ++i) {
+        const int q = base + i;
+        head[i] = q < n && (q == 0 || k[i] != (i == 0 ? prev : k[i - 1]));
+        c += head[i] ? 1u : 0u;
+    }
+    uint32_t tot;
+    uint32_t r = block_exclusive_scan_256(c, s_wave, tot) + tile_first_run[blockIdx.x];
+#pragma unroll
+    for (int i = 0; i < kRlPerThread; ++i) {
+        const int q = base + i;
+        if (q < n) {
+            if ((q & (kChunk - 1)) == 0)
+                chunk_first_run[q / kChunk] = (int32_t)r;
+            if (head[i]) {
+                unique_keys[r] = k[i];
+                seg_offsets[r] = q;
+                ++r;
+            }
+            if (q == n - 1) {
+                seg_offsets[r] = n;
+                chunk_first_run[num_chunks] = (int32_t)r;
+                counters->num_unique = (int64_t)r;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- fused aggregation + row-wise AdaGrad
+//
+// Section 5.1: all gradients of one row are aggregated on chip and the optimizer runs once per row.
+// Section 5.2: m += mean_d(G_d^2); w -= lr * G / (sqrt(m) + eps)  (updated moment, eps outside the root).
+//
+// Each wavefront owns kChunk consecutive sorted positions and every run that STARTS inside them; a
+// run of at most kLongRun lookups is followed past the chunk's end and finished by its owner, so the
+// common case needs no scratch.  A longer run is cut at chunk borders: every chunk it touches writes
+// one fp32 partial row to the workspace and the run is queued for the fix-up kernel, which adds the
+// partials in chunk order and applies the single update.  Either way each touched row is read,
+// updated and written exactly once, and the summation order is fixed (run-to-run deterministic).
+
+__device__ __forceinline__ int find_table(const uint32_t* __restrict__ row_base, int T, uint32_t key)
+{
+    int a = 0, c = T;  // row_base[a] <= key < row_base[c]
+    while (c - a > 1) {
+        const int mid = (a + c) >> 1;
+        if (row_base[mid] <= key)
+            a = mid;
+        else
+            c = mid;
+    }
+    return a;
+}
+
+// Sum of the fp32 rows `rowptr(i)` for i in [p0, p1); 4 floats per lane, up to 2 column blocks.
+// After the butterfly every lane group holds the full sums.
+template <typename RowPtr>
+__device__ __forceinline__ void gather_sum(RowPtr rowptr, int p0, int p1, int D, int lprl, int lane,
+                                           float (&acc)[2][4])
+{
+    const int LPR = 1 << lprl;
+    const int G = kWave >> lprl;
+    const int sub = lane & (LPR - 1);
+    const int grp = lane >> lprl;
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            acc[k][e] = 0.f;
+    for (int i0 = p0; i0 < p1; i0 += G * kBwdUnroll) {
+        float4 v[kBwdUnroll][2];
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u) {
+            const int i = i0 + u * G + grp;
+            const bool ok = i < p1;
+            const float* rp = rowptr(ok ? i : p0);
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int e0 = (sub + k * LPR) * 4;
+                v[u][k] = (ok && e0 < D) ? *reinterpret_cast<const float4*>(rp + e0)
+                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u)
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                acc[k][0] += v[u][k].x;
+                acc[k][1] += v[u][k].y;
+                acc[k][2] += v[u][k].z;
+                acc[k][3] += v[u][k].w;
+            }
+    }
+    for (int s = LPR; s < kWave; s <<= 1) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                acc[k][e] += __shfl_xor(acc[k][e], s);
+    }
+}
+
+template <typename WT>
+__device__ __forceinline__ void apply_rowwise_adagrad(WT* __restrict__ wrow, float* __restrict__ mptr,
+                                                      const float (&acc)[2][4], int D, int lprl,
+                                                      int lane, float lr, float eps)
+{
+    const int LPR = 1 << lprl;
+    const int sub = lane & (LPR - 1);
+    const int grp = lane >> lprl;
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int e0 = (sub + k * LPR) * 4;
+        if (e0 < D)
+            ss += acc[k][0] * acc[k][0] + acc[k][1] * acc[k][1] + acc[k][2] * acc[k][2] +
+                  acc[k][3] * acc[k][3];
+    }
+    for (int s = 1; s < LPR; s <<= 1)
+        ss += __shfl_xor(ss, s);
+    const float m_new = *mptr + ss / (float)D;
+    const float scale = lr / (sqrtf(m_new) + eps);
+    if (grp == 0) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int e0 = (sub + k * LPR) * 4;
+            if (e0 < D) {
+                float w[4];
+                RowIO<WT, 4>::load(wrow + e0, w);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] -= scale * acc[k][e];
+                RowIO<WT, 4>::store(wrow + e0, w);
+            }
+        }
+    }
+    // every lane has read *mptr above; the store is ordered after those loads within the wavefront
+    if (lane == 0)
+        *mptr = m_new;
+}
+
+__device__ __forceinline__ void store_partial(float* __restrict__ dst, const float (&acc)[2][4], int D,
+                                              int lprl, int lane)
+{
+    const int LPR = 1 << lprl;
+    const int sub = lane & (LPR - 1);
+    if ((lane >> lprl) == 0) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int e0 = (sub + k * LPR) * 4;
+            if (e0 < D)
+                *reinterpret_cast<float4*>(dst + e0) =
+                    make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
+        }
+    }
+}
+
+struct BwdArgs {
+    const TableMeta* meta;
+    const uint32_t* row_base;
+    const uint32_t* sorted_keys;
+    const int32_t* sorted_vals;
+    const uint32_t* unique_keys;
+    const int32_t* seg_offsets;
+    const int32_t* chunk_first_run;
+    Counters* counters;
+    const float* grad_out;
+    void* weights;
+    float* moments;
+    float* partials;      // [num_chunks][2][dpad]
+    uint32_t* long_list;
+    int32_t n;
+    int32_t num_chunks;
+    int32_t T;
+    int32_t sumD;
+    int32_t dpad;
+    float lr;
+    float eps;
+};
+
+template <typename WT>
+__global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int k = uniform(blockIdx.x * (kBwdThreads / kWave) + (threadIdx.x >> 6));
+    if (k >= a.num_chunks)
+        return;
+    const int q0 = k * kChunk;
+    const int q1 = min(a.n, q0 + kChunk);
+    const int ub = a.chunk_first_run[k];
+    const int ue = a.chunk_first_run[k + 1];
+    const int U = (int)a.counters->num_unique;
+    WT* __restrict__ weights = static_cast<WT*>(a.weights);
+    const int32_t* __restrict__ vals = a.sorted_vals;
+    const int64_t sumD = a.sumD;
+    float acc[2][4];
+
+    int t = -1;
+    TableMeta m;
+    auto seek_table = [&](uint32_t key) {
+        if (t < 0 || key < a.row_base[t] || key >= a.row_base[t + 1]) {
+            t = find_table(a.row_base, a.T, key);
+            m = a.meta[t];
+        }
+    };
+
+    // the run that is already open at q0: only its long form leaves work here
+    const bool incoming = (ub >= U) || (a.seg_offsets[ub] > q0);
+    if (incoming) {
+        const int u0 = ub - 1;
+        const int s0 = a.seg_offsets[u0];
+        const int e0 = a.seg_offsets[u0 + 1];
+        if (e0 - s0 > kLongRun) {
+            seek_table(a.unique_keys[u0]);
+            const float* gb = a.grad_out + m.col;
+            gather_sum([&](int i) { return gb + (int64_t)vals[i] * sumD; }, q0, min(e0, q1), m.dim,
+                       m.lpr_bwd, lane, acc);
+            store_partial(a.partials + ((int64_t)k * 2 + 0) * a.dpad, acc, m.dim, m.lpr_bwd, lane);
+        }
+    }
+
+    for (int ubase = ub; ubase < ue; ubase += kWave) {
+        const int nb = min(kWave, ue - ubase);
+        const int my_s = lane < nb ? a.seg_offsets[ubase + lane] : 0;
+        const int my_e = lane < nb ? a.seg_offsets[ubase + lane + 1] : 0;
+        const uint32_t my_key = lane < nb ? a.unique_keys[ubase + lane] : 0u;
+        for (int r = 0; r < nb; ++r) {
+            const int s = __builtin_amdgcn_readlane(my_s, r);
+            const int e = __builtin_amdgcn_readlane(my_e, r);
+            const uint32_t key = (uint32_t)__builtin_amdgcn_readlane((int)my_key, r);
+            seek_table(key);
+            const float* gb = a.grad_out + m.col;
+            if (e - s <= kLongRun) {
+                gather_sum([&](int i) { return gb + (int64_t)vals[i] * sumD; }, s, e, m.dim, m.lpr_bwd,
+                           lane, acc);
+                apply_rowwise_adagrad<WT>(weights + m.woff + (int64_t)(key - m.rbase) * m.dim,
+                                          a.moments + key, acc, m.dim, m.lpr_bwd, lane, a.lr, a.eps);
+            } else {
+                gather_sum([&](int i) { return gb + (int64_t)vals[i] * sumD; }, s, min(e, q1), m.dim,
+                           m.lpr_bwd, lane, acc);
+                store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, m.dim, m.lpr_bwd, lane);
+                if (lane == 0) {
+                    const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
+                    a.long_list[slot] = (uint32_t)(ubase + r);
+                }
+            }
+        }
+    }
+}
+
+// One wavefront per queued long run: adds the per-chunk partial rows in chunk order (first the
+// piece written by the chunk where the run starts, then one piece per following chunk) and applies
+// the run's single AdaGrad step.
+template <typename WT>
+__global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave_global = uniform(blockIdx.x * (kBwdThreads / kWave) + (threadIdx.x >> 6));
+    const int wave_total = gridDim.x * (kBwdThreads / kWave);
+    const int cnt = (int)a.counters->long_count;
+    WT* __restrict__ weights = static_cast<WT*>(a.weights);
+    float acc[2][4];
+    for (int i = wave_global; i < cnt; i += wave_total) {
+        const int u = (int)a.long_list[i];
+        const int s = a.seg_offsets[u];
+        const int e = a.seg_offsets[u + 1];
+        const uint32_t key = a.unique_keys[u];
+        const int t = find_table(a.row_base, a.T, key);
+        const TableMeta m = a.meta[t];
+        const int k0 = s / kChunk;
+        const int k1 = (e - 1) / kChunk;
+        const float* pbase = a.partials;
+        const int64_t dpad = a.dpad;
+        gather_sum(
+            [&](int c) { return pbase + ((int64_t)(k0 + c) * 2 + (c == 0 ? 1 : 0)) * dpad; }, 0,
+            k1 - k0 + 1, m.dim, m.lpr_bwd, lane, acc);
+        apply_rowwise_adagrad<WT>(weights + m.woff + (int64_t)(key - m.rbase) * m.dim, a.moments + key,
+                                  acc, m.dim, m.lpr_bwd, lane, a.lr, a.eps);
+    }
+}
+
+// ---------------------------------------------------------------- input validation (slow path)
+
+__global__ __launch_bounds__(256) void check_inputs_kernel(
+    const TableMeta* __restrict__ meta, const uint32_t* __restrict__ row_base,
+    const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets, int64_t num_indices,
+    int32_t B, int32_t num_bags, Counters* __restrict__ counters)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= num_bags)
+        return;
+    uint32_t flags = 0;
+    const int64_t lo = offsets[j], hi = offsets[j + 1];
+    if ((j == 0 && lo != 0) || (j == num_bags - 1 && hi != num_indices) || lo > hi || lo < 0 ||
+        hi > num_indices) {
+        flags |= 1u;
+    } else {
+        const int t = j / B;
+        const int64_t H = (int64_t)row_base[t + 1] - (int64_t)row_base[t];
+        for (int64_t p = lo; p < hi; ++p) {
+            const int64_t r = indices[p];
+            if (r < 0 || r >= H)
+                flags |= 2u;
+        }
+    }
+    (void)meta;
+    if (flags)
+        atomicOr(&counters->check_flags, flags);
+}
+
+__global__ void clear_counters_kernel(Counters* counters)
+{
+    counters->num_unique = 0;
+    counters->long_count = 0;
+    counters->check_flags = 0;
+}
+
+}  // namespace tbe

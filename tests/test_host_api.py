@@ -1,0 +1,94 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol include/tbe.h declares, and
+its host-side logic (config validation, layout tables, workspace sizing, error strings) behaves as
+the header says.  No kernel is launched and no device memory is touched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2104_05158_amd import tbe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tbe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tbe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert set(names) == set(tbe.EXPORTED)
+    L = ctypes.CDLL(tbe.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(tbe, "_lib", None)
+    monkeypatch.setattr(tbe, "LIB_PATH", "/nonexistent/libtbe.so")
+    with pytest.raises(ImportError):
+        tbe.lib()
+
+
+def test_status_strings():
+    seen = {tbe.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert tbe.status_string(99) == "unknown status"
+
+
+def test_create_validates_config():
+    ok = lambda *a, **k: tbe.tbe_create(*a, **k)[0]
+    assert ok([10], [8], 0, 4, 100) == tbe.TBE_OK
+    assert ok([], [], 0, 4, 100) == tbe.TBE_ERR_INVALID_ARG
+    assert ok([0], [8], 0, 4, 100) == tbe.TBE_ERR_INVALID_ARG
+    assert ok([10], [0], 0, 4, 100) == tbe.TBE_ERR_INVALID_ARG
+    assert ok([10], [8], 0, -1, 100) == tbe.TBE_ERR_INVALID_ARG
+    assert ok([10], [8], 0, 4, -1) == tbe.TBE_ERR_INVALID_ARG
+    assert ok([10], [6], 0, 4, 100) == tbe.TBE_ERR_UNSUPPORTED          # dim not a multiple of 4
+    assert ok([10], [516], 0, 4, 100) == tbe.TBE_ERR_UNSUPPORTED        # dim too large
+    assert ok([10], [8], 2, 4, 100) == tbe.TBE_ERR_UNSUPPORTED          # unknown storage type
+    assert ok([10], [8], 0, 4, 100, pooling=1) == tbe.TBE_ERR_UNSUPPORTED
+    assert ok([2 ** 31, 2 ** 31], [8, 8], 0, 4, 100) == tbe.TBE_ERR_UNSUPPORTED   # 2^32 rows
+    assert ok([10], [8], 0, 4, 2 ** 31) == tbe.TBE_ERR_UNSUPPORTED
+    assert ok([10] * 4, [8] * 4, 0, 2 ** 30, 100) == tbe.TBE_ERR_UNSUPPORTED     # T*B overflows
+    assert tbe.lib().tbe_create(None, None) == tbe.TBE_ERR_INVALID_ARG
+    assert tbe.tbe_destroy(None) == tbe.TBE_OK
+
+
+def test_layout_tables_and_sizes():
+    rows, dims = [10, 3, 7], [8, 128, 4]
+    for dtype, es in ((0, 4), (1, 2)):
+        rc, h = tbe.tbe_create(rows, dims, dtype, 16, 1000)
+        assert rc == tbe.TBE_OK
+        rc, q = tbe.tbe_query_sizes(h, 3)
+        assert rc == tbe.TBE_OK
+        assert q["weight_offsets"].tolist() == [0, 80, 80 + 384, 80 + 384 + 28]
+        assert q["state_offsets"].tolist() == [0, 10, 13, 20]
+        assert q["out_col_offsets"].tolist() == [0, 8, 136, 140]
+        assert q["weight_bytes"] == (80 + 384 + 28) * es and q["state_bytes"] == 80
+        # the sort needs two (key, payload) pairs of max_indices entries at the least
+        assert q["workspace_bytes"] >= 4 * 4 * 1000 and q["workspace_bytes"] % 256 == 0
+        tbe.tbe_destroy(h)
+    # workspace grows with max_indices, and is computed (not allocated) for the largest config
+    rc, h = tbe.tbe_create([5 * 10 ** 7] * 8, [128] * 8, 1, 65536, 800_000_000)
+    assert rc == tbe.TBE_OK
+    rc, q = tbe.tbe_query_sizes(h, 8)
+    assert 16 * 800_000_000 < q["workspace_bytes"] < 40 * 800_000_000
+    tbe.tbe_destroy(h)
+
+
+def test_calls_on_unbound_or_null_handles():
+    rc, h = tbe.tbe_create([10], [8], 0, 4, 100)
+    L = tbe.lib()
+    assert L.tbe_forward(h, None, None, 0, 0, None, None) == tbe.TBE_ERR_NOT_BOUND
+    assert L.tbe_backward_rowwise_adagrad(h, None, None, 0, 0, None, 0.1, 1e-8, None) == tbe.TBE_ERR_NOT_BOUND
+    assert tbe.tbe_backward_artifacts(h)[0] == tbe.TBE_ERR_NOT_BOUND
+    assert L.tbe_forward(None, None, None, 0, 0, None, None) == tbe.TBE_ERR_INVALID_ARG
+    assert L.tbe_bind(h, None, None, None, 0) == tbe.TBE_ERR_INVALID_ARG
+    assert L.tbe_query_sizes(None, None, None, None, None, None, None) == tbe.TBE_ERR_INVALID_ARG
+    assert tbe.tbe_last_hip_error(h) == ""
+    tbe.tbe_destroy(h)
