@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the table-batched embedding-bag hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch: tbe_forward, then
+tbe_backward_rowwise_adagrad (key build, radix sort, run-length, fused reduce + row-wise AdaGrad,
+long-run fix-up) on the same batch.  Inputs, weights and optimizer state are resident in HBM before
+the timed region; a rotation of pre-generated batches (different seeds) is used so that no step
+re-reads the previous step's index stream.
+
+Prints ONE JSON line: lookups/s of fwd+bwd (whole job = this one GPU), plus
+  roofline      -- the dominant kernel's algorithmic bytes per launch / its mean launch duration,
+                   measured with HIP events recorded by the library on the launch stream
+  cpu_baseline  -- the CPU oracle, as it stands, timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..4 (default 2)")
+    ap.add_argument("--paper-membench", choices=["fp32", "fp16"], default=None,
+                    help="run the Appendix A memory-benchmark shape instead of a config")
+    ap.add_argument("--batch", type=int, default=None, help="batch override (memory benchmark sweep)")
+    ap.add_argument("--rotation", type=int, default=4, help="number of pre-generated batches")
+    ap.add_argument("--flush", action="store_true", help="write a 1 GiB scratch between steps (cold caches)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-lookups", type=float, default=4e6)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference dispatch for HBM counter scaling)")
+    ap.add_argument("--fwd-only", action="store_true")
+    return ap.parse_args()
+
+
+def per_table_counts(spec, batch):
+    off = batch.offsets
+    B = spec.batch
+    bounds = off[:: B][: spec.T + 1] if B > 0 else off
+    return np.diff(bounds.cpu().numpy())
+
+
+def kernel_bytes(spec, n_t, u_t, key_passes):
+    """Algorithmic bytes one launch of each kernel must move (logical: every lookup counted)."""
+    sw = 4 if spec.dtype == 0 else 2
+    D = spec.dims.astype(np.float64)
+    B = float(spec.batch)
+    N = float(n_t.sum())
+    U = float(u_t.sum())
+    bags = float(spec.T) * B
+    fwd = float((n_t * (D * sw + 4)).sum() + (B * (8 + 4 * D)).sum())
+    upd = float(N * 4 + (n_t * 4 * D).sum() + (u_t * (2 * D * sw + 8)).sum() + U * 8)
+    return {
+        "forward": fwd,
+        "build_keys": N * 4 + bags * 8 + N * 8,
+        "radix_hist": N * 4,
+        "radix_scatter": N * 16,
+        "radix_scan": 0.0,
+        "runlength": N * 8 + U * 8,
+        "reduce_update": upd,
+        "long_fixup": 0.0,
+        "compulsory_forward": float((u_t * D * sw).sum() + N * 4 + (B * (8 + 4 * D)).sum()),
+    }
+
+
+def cpu_baseline(spec, batch, weights, grad, target_lookups):
+    """Times the CPU oracle (single thread, as it stands) on the first tables of the workload whose
+    lookups add up to about `target_lookups`; exact for those tables because tables are independent."""
+    import torch
+
+    from oracle import tbe_oracle as orc
+
+    B = spec.batch
+    n_t = per_table_counts(spec, batch)
+    order = np.arange(spec.T)
+    take, tot, wbytes = [], 0, 0
+    for t in order:
+        tb = int(spec.rows[t]) * int(spec.dims[t]) * (4 if spec.dtype == 0 else 2)
+        if take and (tot + n_t[t] > 1.5 * target_lookups or wbytes + tb > 24e9):
+            continue
+        take.append(int(t))
+        tot += int(n_t[t])
+        wbytes += tb
+        if tot >= target_lookups:
+            break
+    take.sort()
+    woffs = np.concatenate([[0], np.cumsum(spec.rows * spec.dims.astype(np.int64))])
+    cols = np.concatenate([[0], np.cumsum(spec.dims)])
+    off = batch.offsets
+    idx_parts, len_parts, w_parts, g_parts = [], [], [], []
+    for t in take:
+        lo, hi = int(off[t * B]), int(off[(t + 1) * B])
+        idx_parts.append(batch.indices[lo:hi].cpu().numpy())
+        len_parts.append(np.diff(off[t * B:(t + 1) * B + 1].cpu().numpy()))
+        w_parts.append(weights[int(woffs[t]):int(woffs[t + 1])].cpu().numpy())
+        g_parts.append(grad[:, int(cols[t]):int(cols[t + 1])].cpu().numpy())
+    rows = spec.rows[take]
+    dims = spec.dims[take]
+    indices = np.concatenate(idx_parts).astype(np.int32)
+    offsets = np.zeros(len(take) * B + 1, np.int64)
+    offsets[1:] = np.cumsum(np.concatenate(len_parts))
+    w = np.concatenate(w_parts)
+    g = np.ascontiguousarray(np.concatenate(g_parts, axis=1))
+    m = np.zeros(int(rows.sum()), np.float32)
+    orc.build()
+    t0 = time.perf_counter()
+    orc.forward(rows, dims, spec.dtype, w, indices, offsets, B)
+    t1 = time.perf_counter()
+    orc.backward_rowwise_adagrad(rows, dims, spec.dtype, w, m, indices, offsets, B, g, spec.lr, spec.eps)
+    t2 = time.perf_counter()
+    n = int(offsets[-1])
+    return {
+        "value": n / (t2 - t0),
+        "unit": "lookups/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"tables {take[0]}..{take[-1]} ({len(take)} of {spec.T}) of the same batch, {n} lookups, "
+                  f"fwd {t1 - t0:.2f}s + bwd {t2 - t1:.2f}s; plain C -O2, fp64 accumulation",
+        "fwd_s": t1 - t0,
+        "bwd_s": t2 - t1,
+        "lookups": n,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (the operator runs on one GPU's share of the tables; "
+              "no collectives are part of it). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2104_05158_amd import tbe
+    from paper_2104_05158_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tbe.lib()  # fail loudly if the HIP library is missing
+
+    if args.paper_membench:
+        spec = wl.paper_memory_benchmark(0 if args.paper_membench == "fp32" else 1, args.batch or 4096)
+    else:
+        spec = wl.config(args.config)
+        if args.batch:
+            spec.batch = args.batch
+    t_setup = time.perf_counter()
+    weights = wl.make_weights(spec, dev)
+    batches = [wl.make_batch(spec, dev, it=i) for i in range(max(1, args.rotation))]
+    grad = wl.make_grad(spec, dev)
+    nmax = max(b.num_indices for b in batches)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, spec.batch, nmax, device=dev,
+                                       weights=weights)
+    out = torch.empty(spec.batch, spec.sumD, dtype=torch.float32, device=dev)
+    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if args.flush else None
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    def step(i):
+        b = batches[i % len(batches)]
+        if flush_buf is not None:
+            flush_buf.fill_(i & 0xFF)
+        op.forward(b.indices, b.offsets, spec.batch, out=out, num_indices=b.num_indices)
+        if not args.fwd_only:
+            op.backward_rowwise_adagrad(b.indices, b.offsets, spec.batch, grad, spec.lr, spec.eps,
+                                        num_indices=b.num_indices)
+
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        a.normal_()
+        c = torch.empty_like(a)
+        c.copy_(a)
+        torch.cuda.synchronize()
+        del a, c
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    op.profile_enable(args.steps + 1)
+    lookups = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        lookups += batches[(args.warmup + i) % len(batches)].num_indices
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = op.profile_read()
+    op.profile_enable(0)
+
+    # workload statistics of the last batch used (for the byte model)
+    last = batches[(args.warmup + args.steps - 1) % len(batches)]
+    n_t = per_table_counts(spec, last).astype(np.float64)
+    if args.fwd_only:
+        u_t = np.zeros(spec.T)
+        num_unique = 0
+    else:
+        art = op.artifacts()
+        num_unique = art["num_unique"]
+        R = torch.tensor(np.concatenate([[0], np.cumsum(spec.rows)]), device=dev)
+        uk = art["unique_keys"].to(torch.int64) & 0xFFFFFFFF
+        tab = torch.searchsorted(R, uk, right=True) - 1
+        u_t = torch.bincount(tab, minlength=spec.T).cpu().numpy().astype(np.float64)
+    key_bits = max(1, int(np.ceil(np.log2(max(2, spec.total_rows)))))
+    passes = (key_bits + 7) // 8
+    kb = kernel_bytes(spec, n_t, u_t, passes)
+
+    kernels = {}
+    for name, (launches, ms) in prof.items():
+        if launches:
+            per = ms / launches
+            per_step = ms / args.steps
+            kernels[name] = {"launches_per_step": launches / args.steps, "ms_per_launch": round(per, 5),
+                             "ms_per_step": round(per_step, 5),
+                             "algorithmic_GBps": round(kb.get(name, 0.0) / (per * 1e-3) / 1e9, 1) if per > 0 else None}
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    dom_ms = kernels[dominant]["ms_per_launch"]
+    achieved = kb[dominant] / (dom_ms * 1e-3) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": kb[dominant], "ms_per_launch": dom_ms}
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            tr = json.load(open(traffic_file)).get(spec.name, {}).get(dominant)
+            if tr is not None:
+                roofline["traffic"] = tr
+        except Exception:
+            pass
+
+    ms_per_step = elapsed / args.steps * 1e3
+    fwd_ms = kernels.get("forward", {}).get("ms_per_step", 0.0)
+    bwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k != "forward")
+    result = {
+        "metric": "tbe_fwd_bwd_rowwise_adagrad_lookups_per_s" if not args.fwd_only else "tbe_fwd_lookups_per_s",
+        "value": lookups / elapsed,
+        "unit": "lookups/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": spec.name,
+            "tables": spec.T,
+            "batch": spec.batch,
+            "storage": "fp32" if spec.dtype == 0 else "fp16",
+            "lookups_per_step": lookups / args.steps,
+            "unique_rows_last_step": num_unique,
+            "table_bytes": spec.weight_bytes,
+            "index_dist": spec.index_dist if spec.index_dist == "uniform" else f"zipf({spec.zipf_s})",
+            "rotation": len(batches),
+            "cache_flush": bool(args.flush),
+        },
+        "roofline": roofline,
+        "kernels": kernels,
+        "fwd_ms": fwd_ms,
+        "bwd_ms": round(bwd_ms, 5),
+        "logical_GBps_fwd": round(kb["forward"] / (fwd_ms * 1e-3) / 1e9, 1) if fwd_ms else None,
+        "compulsory_GBps_fwd": round(kb["compulsory_forward"] / (fwd_ms * 1e-3) / 1e9, 1) if fwd_ms and not args.fwd_only else None,
+        "setup_s": round(setup_s, 2),
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(spec, last, weights, grad, args.cpu_sample_lookups)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
