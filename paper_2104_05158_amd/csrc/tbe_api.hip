@@ -317,7 +317,7 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
         m.dim = h->dims[t];
         m.col = c;
         m.lpr_fwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], h->fwd_epl)));
-        m.lpr_bwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], 4)));
+        m.lpr_bwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], 8)));
         m.pad = 0;
         w += h->rows[t] * (int64_t)h->dims[t];
         s += h->rows[t];

@@ -31,10 +31,11 @@ constexpr int kScanTile = kScanThreads * kScanPerThread;      // 4096
 constexpr int kRlThreads = 256;
 constexpr int kRlPerThread = 16;
 constexpr int kRlTile = kRlThreads * kRlPerThread;            // 4096 sorted positions
-constexpr int kChunk = 256;               // sorted positions owned by one wavefront in the update
+constexpr int kChunk = 128;               // sorted positions owned by one wavefront in the update
 constexpr int kLongRun = 512;             // runs longer than this are split over their chunks
 constexpr int kBwdThreads = 256;          // 4 wavefronts = 4 chunks per workgroup
-constexpr int kBwdUnroll = 4;
+constexpr int kBwdUnroll = 4;             // gradient rows in flight per lane group (long runs)
+constexpr int kShortRun = 4;              // runs up to this length are handled one per lane group
 constexpr int kMaxDim = 512;
 
 struct TableMeta {      // 32 bytes, one per table, in the workspace head
@@ -43,7 +44,7 @@ struct TableMeta {      // 32 bytes, one per table, in the workspace head
     int32_t dim;        // D_t
     int32_t col;        // first output column
     int32_t lpr_fwd;    // log2 lanes per row, forward (EPL elements per lane)
-    int32_t lpr_bwd;    // log2 lanes per row, backward (4 floats per lane)
+    int32_t lpr_bwd;    // log2 lanes per row, backward (2 x 4 floats per lane)
     int32_t pad;
 };
 
@@ -611,12 +612,20 @@ __global__ __launch_bounds__(kRlThreads) void runlength_write_kernel(
 // Section 5.1: all gradients of one row are aggregated on chip and the optimizer runs once per row.
 // Section 5.2: m += mean_d(G_d^2); w -= lr * G / (sqrt(m) + eps)  (updated moment, eps outside the root).
 //
-// Each wavefront owns kChunk consecutive sorted positions and every run that STARTS inside them; a
-// run of at most kLongRun lookups is followed past the chunk's end and finished by its owner, so the
-// common case needs no scratch.  A longer run is cut at chunk borders: every chunk it touches writes
-// one fp32 partial row to the workspace and the run is queued for the fix-up kernel, which adds the
-// partials in chunk order and applies the single update.  Either way each touched row is read,
-// updated and written exactly once, and the summation order is fixed (run-to-run deterministic).
+// Each wavefront owns kChunk consecutive sorted positions and every run that STARTS inside them.
+// The chunk's run descriptors and payloads are staged in LDS once.  Lane mapping: a row of D floats
+// is covered by LPR = pow2ceil(D/8) lanes, two float4 blocks per lane, so G = 64/LPR rows are
+// fetched per load instruction.
+//   * runs of at most kShortRun lookups (the vast majority) are handled G at a time, one per lane
+//     group: all their gradient rows, weight rows and moments are requested before anything is
+//     consumed, the sum stays inside the group, and all groups apply their update together;
+//   * longer runs use the whole wavefront (groups take alternate lookups, xor butterfly at the end);
+//     up to kLongRun lookups the owner follows the run past its chunk and finishes it;
+//   * a run longer than kLongRun is cut at chunk borders: every chunk it touches writes one fp32
+//     partial row to the workspace and the run is queued for the fix-up kernel, which adds the
+//     partials in chunk order and applies the single update.
+// Either way each touched row is read, updated and written exactly once, nothing is accumulated
+// with atomics, and the summation order is fixed: results are bit-identical run to run.
 
 __device__ __forceinline__ int find_table(const uint32_t* __restrict__ row_base, int T, uint32_t key)
 {
@@ -629,109 +638,6 @@ __device__ __forceinline__ int find_table(const uint32_t* __restrict__ row_base,
             c = mid;
     }
     return a;
-}
-
-// Sum of the fp32 rows `rowptr(i)` for i in [p0, p1); 4 floats per lane, up to 2 column blocks.
-// After the butterfly every lane group holds the full sums.
-template <typename RowPtr>
-__device__ __forceinline__ void gather_sum(RowPtr rowptr, int p0, int p1, int D, int lprl, int lane,
-                                           float (&acc)[2][4])
-{
-    const int LPR = 1 << lprl;
-    const int G = kWave >> lprl;
-    const int sub = lane & (LPR - 1);
-    const int grp = lane >> lprl;
-#pragma unroll
-    for (int k = 0; k < 2; ++k)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            acc[k][e] = 0.f;
-    for (int i0 = p0; i0 < p1; i0 += G * kBwdUnroll) {
-        float4 v[kBwdUnroll][2];
-#pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u) {
-            const int i = i0 + u * G + grp;
-            const bool ok = i < p1;
-            const float* rp = rowptr(ok ? i : p0);
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const int e0 = (sub + k * LPR) * 4;
-                v[u][k] = (ok && e0 < D) ? *reinterpret_cast<const float4*>(rp + e0)
-                                         : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u)
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                acc[k][0] += v[u][k].x;
-                acc[k][1] += v[u][k].y;
-                acc[k][2] += v[u][k].z;
-                acc[k][3] += v[u][k].w;
-            }
-    }
-    for (int s = LPR; s < kWave; s <<= 1) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                acc[k][e] += __shfl_xor(acc[k][e], s);
-    }
-}
-
-template <typename WT>
-__device__ __forceinline__ void apply_rowwise_adagrad(WT* __restrict__ wrow, float* __restrict__ mptr,
-                                                      const float (&acc)[2][4], int D, int lprl,
-                                                      int lane, float lr, float eps)
-{
-    const int LPR = 1 << lprl;
-    const int sub = lane & (LPR - 1);
-    const int grp = lane >> lprl;
-    float ss = 0.f;
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int e0 = (sub + k * LPR) * 4;
-        if (e0 < D)
-            ss += acc[k][0] * acc[k][0] + acc[k][1] * acc[k][1] + acc[k][2] * acc[k][2] +
-                  acc[k][3] * acc[k][3];
-    }
-    for (int s = 1; s < LPR; s <<= 1)
-        ss += __shfl_xor(ss, s);
-    const float m_new = *mptr + ss / (float)D;
-    const float scale = lr / (sqrtf(m_new) + eps);
-    if (grp == 0) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int e0 = (sub + k * LPR) * 4;
-            if (e0 < D) {
-                float w[4];
-                RowIO<WT, 4>::load(wrow + e0, w);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    w[e] -= scale * acc[k][e];
-                RowIO<WT, 4>::store(wrow + e0, w);
-            }
-        }
-    }
-    // every lane has read *mptr above; the store is ordered after those loads within the wavefront
-    if (lane == 0)
-        *mptr = m_new;
-}
-
-__device__ __forceinline__ void store_partial(float* __restrict__ dst, const float (&acc)[2][4], int D,
-                                              int lprl, int lane)
-{
-    const int LPR = 1 << lprl;
-    const int sub = lane & (LPR - 1);
-    if ((lane >> lprl) == 0) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int e0 = (sub + k * LPR) * 4;
-            if (e0 < D)
-                *reinterpret_cast<float4*>(dst + e0) =
-                    make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
-        }
-    }
 }
 
 struct BwdArgs {
@@ -757,31 +663,175 @@ struct BwdArgs {
     float eps;
 };
 
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void acc4(float (&a)[4], const float4 v)
+{
+    a[0] += v.x; a[1] += v.y; a[2] += v.z; a[3] += v.w;
+}
+
+// Whole-wavefront sum of the fp32 rows rowptr(i), i in [p0, p1).  Afterwards every lane group holds
+// the complete sums (lane `sub` of a group: elements (sub + k*LPR)*4 .. +3, k = 0, 1).
+template <typename RowPtr>
+__device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, int D, int lprl, int lane,
+                                                float (&acc)[2][4])
+{
+    const int LPR = 1 << lprl;
+    const int G = kWave >> lprl;
+    const int sub = lane & (LPR - 1);
+    const int grp = lane >> lprl;
+    const int e0 = sub * 4, e1 = (sub + LPR) * 4;
+    const bool c0 = e0 < D, c1 = e1 < D;
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            acc[k][e] = 0.f;
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = p0; i0 < p1; i0 += G * kBwdUnroll) {
+        float4 v[kBwdUnroll][2];
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u) {
+            const int i = i0 + u * G + grp;
+            const bool ok = i < p1;
+            const float* rp = rowptr(ok ? i : p0);
+            v[u][0] = (ok && c0) ? ld4(rp + e0) : z;
+            v[u][1] = (ok && c1) ? ld4(rp + e1) : z;
+        }
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u) {
+            acc4(acc[0], v[u][0]);
+            acc4(acc[1], v[u][1]);
+        }
+    }
+    for (int s = LPR; s < kWave; s <<= 1) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                acc[k][e] += __shfl_xor(acc[k][e], s);
+    }
+}
+
+// The AdaGrad epilogue for the row held by this lane's group (w: the row's old values, already loaded).
+template <typename WT>
+__device__ __forceinline__ void adagrad_epilogue(WT* __restrict__ wrow, float* __restrict__ mptr, float m_old,
+                                                 float (&w)[2][4], const float (&acc)[2][4], int D, int lprl,
+                                                 int lane, bool writer, float lr, float eps)
+{
+    const int LPR = 1 << lprl;
+    const int sub = lane & (LPR - 1);
+    const int e0 = sub * 4, e1 = (sub + LPR) * 4;
+    float ss = 0.f;
+    if (e0 < D)
+        ss += acc[0][0] * acc[0][0] + acc[0][1] * acc[0][1] + acc[0][2] * acc[0][2] + acc[0][3] * acc[0][3];
+    if (e1 < D)
+        ss += acc[1][0] * acc[1][0] + acc[1][1] * acc[1][1] + acc[1][2] * acc[1][2] + acc[1][3] * acc[1][3];
+    for (int s = 1; s < LPR; s <<= 1)
+        ss += __shfl_xor(ss, s);
+    const float m_new = m_old + ss / (float)D;
+    const float scale = lr / (sqrtf(m_new) + eps);
+    if (writer) {
+        if (e0 < D) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w[0][e] -= scale * acc[0][e];
+            RowIO<WT, 4>::store(wrow + e0, w[0]);
+        }
+        if (e1 < D) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w[1][e] -= scale * acc[1][e];
+            RowIO<WT, 4>::store(wrow + e1, w[1]);
+        }
+        if (sub == 0)
+            *mptr = m_new;
+    }
+}
+
+template <typename WT>
+__device__ __forceinline__ void load_row(const WT* __restrict__ wrow, int D, int lprl, int lane, bool active,
+                                         float (&w)[2][4])
+{
+    const int LPR = 1 << lprl;
+    const int sub = lane & (LPR - 1);
+    const int e0 = sub * 4, e1 = (sub + LPR) * 4;
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w[k][e] = 0.f;
+    if (active && e0 < D)
+        RowIO<WT, 4>::load(wrow + e0, w[0]);
+    if (active && e1 < D)
+        RowIO<WT, 4>::load(wrow + e1, w[1]);
+}
+
+__device__ __forceinline__ void store_partial(float* __restrict__ dst, const float (&acc)[2][4], int D, int lprl,
+                                              int lane)
+{
+    const int LPR = 1 << lprl;
+    const int sub = lane & (LPR - 1);
+    if ((lane >> lprl) == 0) {
+        if (sub * 4 < D)
+            *reinterpret_cast<float4*>(dst + sub * 4) = make_float4(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+        if ((sub + LPR) * 4 < D)
+            *reinterpret_cast<float4*>(dst + (sub + LPR) * 4) =
+                make_float4(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+    }
+}
+
 template <typename WT>
 __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
 {
+    constexpr int kWaves = kBwdThreads / kWave;
+    __shared__ int32_t s_seg_all[kWaves][kChunk + 2];
+    __shared__ uint32_t s_key_all[kWaves][kChunk + 1];
+    __shared__ int32_t s_val_all[kWaves][kChunk];
+
     const int lane = threadIdx.x & (kWave - 1);
-    const int k = uniform(blockIdx.x * (kBwdThreads / kWave) + (threadIdx.x >> 6));
+    const int wv = threadIdx.x >> 6;
+    const int k = uniform(blockIdx.x * kWaves + wv);
     if (k >= a.num_chunks)
         return;
+    int32_t* s_seg = s_seg_all[wv];
+    uint32_t* s_key = s_key_all[wv];
+    int32_t* s_val = s_val_all[wv];
+
     const int q0 = k * kChunk;
     const int q1 = min(a.n, q0 + kChunk);
     const int ub = a.chunk_first_run[k];
     const int ue = a.chunk_first_run[k + 1];
     const int U = (int)a.counters->num_unique;
+    const int nruns = ue - ub;  // runs that start in [q0, q1): at most kChunk
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     const int32_t* __restrict__ vals = a.sorted_vals;
     const int64_t sumD = a.sumD;
-    float acc[2][4];
 
+    // stage the chunk's run descriptors and payloads (wavefront-private LDS)
+    for (int i = lane; i <= nruns; i += kWave)
+        s_seg[i] = a.seg_offsets[ub + i];
+    for (int i = lane; i < nruns; i += kWave)
+        s_key[i] = a.unique_keys[ub + i];
+    for (int i = lane; i < q1 - q0; i += kWave)
+        s_val[i] = vals[q0 + i];
+    __threadfence_block();
+    __builtin_amdgcn_wave_barrier();
+
+    float acc[2][4];
+    float w[2][4];
     int t = -1;
+    uint32_t t_lo = 1u, t_hi = 0u;  // empty range: first key always seeks
     TableMeta m;
+    m.woff = 0; m.rbase = 0; m.dim = 4; m.col = 0; m.lpr_fwd = 0; m.lpr_bwd = 0; m.pad = 0;
     auto seek_table = [&](uint32_t key) {
-        if (t < 0 || key < a.row_base[t] || key >= a.row_base[t + 1]) {
+        if (key < t_lo || key >= t_hi) {
             t = find_table(a.row_base, a.T, key);
             m = a.meta[t];
+            t_lo = a.row_base[t];
+            t_hi = a.row_base[t + 1];
         }
     };
+    auto payload = [&](int p) { return p < q1 ? s_val[p - q0] : vals[p]; };
 
     // the run that is already open at q0: only its long form leaves work here
     const bool incoming = (ub >= U) || (a.seg_offsets[ub] > q0);
@@ -792,37 +842,86 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         if (e0 - s0 > kLongRun) {
             seek_table(a.unique_keys[u0]);
             const float* gb = a.grad_out + m.col;
-            gather_sum([&](int i) { return gb + (int64_t)vals[i] * sumD; }, q0, min(e0, q1), m.dim,
-                       m.lpr_bwd, lane, acc);
+            wave_gather_sum([&](int i) { return gb + (int64_t)payload(i) * sumD; }, q0, min(e0, q1), m.dim,
+                            m.lpr_bwd, lane, acc);
             store_partial(a.partials + ((int64_t)k * 2 + 0) * a.dpad, acc, m.dim, m.lpr_bwd, lane);
         }
     }
 
-    for (int ubase = ub; ubase < ue; ubase += kWave) {
-        const int nb = min(kWave, ue - ubase);
-        const int my_s = lane < nb ? a.seg_offsets[ubase + lane] : 0;
-        const int my_e = lane < nb ? a.seg_offsets[ubase + lane + 1] : 0;
-        const uint32_t my_key = lane < nb ? a.unique_keys[ubase + lane] : 0u;
-        for (int r = 0; r < nb; ++r) {
-            const int s = __builtin_amdgcn_readlane(my_s, r);
-            const int e = __builtin_amdgcn_readlane(my_e, r);
-            const uint32_t key = (uint32_t)__builtin_amdgcn_readlane((int)my_key, r);
-            seek_table(key);
-            const float* gb = a.grad_out + m.col;
-            if (e - s <= kLongRun) {
-                gather_sum([&](int i) { return gb + (int64_t)vals[i] * sumD; }, s, e, m.dim, m.lpr_bwd,
-                           lane, acc);
-                apply_rowwise_adagrad<WT>(weights + m.woff + (int64_t)(key - m.rbase) * m.dim,
-                                          a.moments + key, acc, m.dim, m.lpr_bwd, lane, a.lr, a.eps);
+    int r = 0;
+    while (r < nruns) {
+        const uint32_t key0 = (uint32_t)uniform((int)s_key[r]);
+        seek_table(key0);
+        const int D = m.dim;
+        const int lprl = m.lpr_bwd;
+        const int s0 = uniform(s_seg[r]);
+        const int len0 = uniform(s_seg[r + 1]) - s0;
+        const float* gb = a.grad_out + m.col;
+        WT* wtab = weights + m.woff;
+        if (len0 > kShortRun) {
+            // ---- one run, whole wavefront
+            WT* wrow = wtab + (int64_t)(key0 - m.rbase) * D;
+            const bool is_long = len0 > kLongRun;
+            const bool writer = (lane >> lprl) == 0;
+            float m_old = 0.f;
+            if (!is_long) {
+                load_row<WT>(wrow, D, lprl, lane, writer, w);
+                m_old = a.moments[key0];
+            }
+            const int e = is_long ? q1 : s0 + len0;
+            wave_gather_sum([&](int i) { return gb + (int64_t)payload(i) * sumD; }, s0, e, D, lprl, lane, acc);
+            if (!is_long) {
+                adagrad_epilogue<WT>(wrow, a.moments + key0, m_old, w, acc, D, lprl, lane, writer, a.lr, a.eps);
             } else {
-                gather_sum([&](int i) { return gb + (int64_t)vals[i] * sumD; }, s, min(e, q1), m.dim,
-                           m.lpr_bwd, lane, acc);
-                store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, m.dim, m.lpr_bwd, lane);
+                store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, D, lprl, lane);
                 if (lane == 0) {
                     const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
-                    a.long_list[slot] = (uint32_t)(ubase + r);
+                    a.long_list[slot] = (uint32_t)(ub + r);
                 }
             }
+            r += 1;
+        } else {
+            // ---- up to G short runs of this table at once, one per lane group
+            const int LPR = 1 << lprl;
+            const int sub = lane & (LPR - 1);
+            const int grp = lane >> lprl;
+            const int rr = r + grp;
+            const bool in_chunk = rr < nruns;
+            const uint32_t key = in_chunk ? s_key[rr] : 0u;
+            const int s = in_chunk ? s_seg[rr] : 0;
+            const int len = in_chunk ? s_seg[rr + 1] - s : 0;
+            const bool fits = in_chunk && key < t_hi && len <= kShortRun;
+            const uint64_t bad = __ballot(!fits);
+            const int first_bad = bad ? (int)__builtin_ctzll(bad) : kWave;
+            const int nb = first_bad >> lprl;  // >= 1: run r itself fits
+            const bool active = grp < nb;
+
+            WT* wrow = wtab + (int64_t)(key - m.rbase) * D;
+            load_row<WT>(wrow, D, lprl, lane, active, w);
+            const float m_old = active ? a.moments[key] : 0.f;
+            const int e0 = sub * 4, e1 = (sub + LPR) * 4;
+            const bool c0 = e0 < D, c1 = e1 < D;
+            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 v[kShortRun][2];
+#pragma unroll
+            for (int u = 0; u < kShortRun; ++u) {
+                const bool ok = active && u < len;
+                const float* rp = gb + (int64_t)(ok ? payload(s + u) : 0) * sumD;
+                v[u][0] = (ok && c0) ? ld4(rp + e0) : z;
+                v[u][1] = (ok && c1) ? ld4(rp + e1) : z;
+            }
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc[kk][e] = 0.f;
+#pragma unroll
+            for (int u = 0; u < kShortRun; ++u) {
+                acc4(acc[0], v[u][0]);
+                acc4(acc[1], v[u][1]);
+            }
+            adagrad_epilogue<WT>(wrow, a.moments + key, m_old, w, acc, D, lprl, lane, active, a.lr, a.eps);
+            r += nb;
         }
     }
 }
@@ -839,6 +938,7 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
     const int cnt = (int)a.counters->long_count;
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     float acc[2][4];
+    float w[2][4];
     for (int i = wave_global; i < cnt; i += wave_total) {
         const int u = (int)a.long_list[i];
         const int s = a.seg_offsets[u];
@@ -850,11 +950,13 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
         const int k1 = (e - 1) / kChunk;
         const float* pbase = a.partials;
         const int64_t dpad = a.dpad;
-        gather_sum(
-            [&](int c) { return pbase + ((int64_t)(k0 + c) * 2 + (c == 0 ? 1 : 0)) * dpad; }, 0,
-            k1 - k0 + 1, m.dim, m.lpr_bwd, lane, acc);
-        apply_rowwise_adagrad<WT>(weights + m.woff + (int64_t)(key - m.rbase) * m.dim, a.moments + key,
-                                  acc, m.dim, m.lpr_bwd, lane, a.lr, a.eps);
+        WT* wrow = weights + m.woff + (int64_t)(key - m.rbase) * m.dim;
+        const bool writer = (lane >> m.lpr_bwd) == 0;
+        load_row<WT>(wrow, m.dim, m.lpr_bwd, lane, writer, w);
+        const float m_old = a.moments[key];
+        wave_gather_sum([&](int c) { return pbase + ((int64_t)(k0 + c) * 2 + (c == 0 ? 1 : 0)) * dpad; }, 0,
+                        k1 - k0 + 1, m.dim, m.lpr_bwd, lane, acc);
+        adagrad_epilogue<WT>(wrow, a.moments + key, m_old, w, acc, m.dim, m.lpr_bwd, lane, writer, a.lr, a.eps);
     }
 }
 

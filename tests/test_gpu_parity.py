@@ -88,7 +88,7 @@ def test_single_hot_row_long_run_path(gpu_device, dtype):
     print("hot", r)
 
 
-@pytest.mark.parametrize("run_len", [255, 256, 257, 511, 512, 513, 768, 1025])
+@pytest.mark.parametrize("run_len", [3, 4, 5, 127, 128, 129, 255, 256, 257, 511, 512, 513, 768, 1025])
 def test_run_lengths_around_chunk_and_long_run_thresholds(gpu_device, run_len):
     # table of 3 rows: row 1 gets exactly run_len lookups, preceded and followed by shorter runs so
     # that the run starts inside a chunk, not on its border
