@@ -208,14 +208,17 @@ tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, in
                             hipStream_t st)
 {
     const int num_bags = h->T * batch;
-    const int per_block = kFwdThreads / kWave;
+    // bags per wavefront: enough to amortise the per-block prologue, few enough to keep >= ~16k
+    // wavefronts in the grid when the batch is small
+    const int bpw = (int)std::min<int64_t>(kFwdMaxBagsPerWave, std::max<int64_t>(1, num_bags / 16384));
+    const int per_block = (kFwdThreads / kWave) * bpw;
     const dim3 grid((unsigned)ceil_div(num_bags, per_block)), block(kFwdThreads);
     const TableMeta* meta = h->ws<TableMeta>(h->off_meta);
     const WT* w = static_cast<const WT*>(h->d_weights);
     const int sumD = (int)h->sumD;
 #define FWD(EPL, KMAX)                                                                              \
     hipLaunchKernelGGL((forward_kernel<WT, EPL, KMAX>), grid, block, 0, st, meta, w, idx, off, out, \
-                       batch, num_bags, sumD)
+                       batch, num_bags, sumD, bpw)
     if constexpr (sizeof(WT) == 4) {
         if (h->fwd_kmax == 1)
             FWD(4, 1);

@@ -19,8 +19,10 @@ namespace tbe {
 constexpr int kWave = 64;
 
 // ---- geometry constants shared by host and device ----
-constexpr int kFwdThreads = 256;          // 4 wavefronts = 4 bags per workgroup
-constexpr int kFwdUnroll = 4;             // row loads in flight per lane group
+constexpr int kFwdThreads = 256;          // 4 wavefronts per workgroup, each with its own block of bags
+constexpr int kFwdUnroll = 4;             // row loads in flight per lane group (8 costs occupancy and is slower)
+constexpr int kFwdStage = 512;            // indices staged in LDS per wavefront
+constexpr int kFwdMaxBagsPerWave = 8;     // measured best on configs 2-4 (4..32 tried)
 constexpr int kKeyBags = 256;             // bags per workgroup in the key build
 constexpr int kSortThreads = 512;         // 8 wavefronts
 constexpr int kSortKeysPerThread = 16;
@@ -109,51 +111,74 @@ struct RowIO<__half, 8> {
 
 // ---------------------------------------------------------------- forward (Section 2, Section 5.1)
 //
-// One wavefront per bag.  The bag's indices are read 64 at a time, coalesced, and handed to the
-// lane groups by shuffle; each group streams whole rows with EPL-element vector loads, kFwdUnroll
-// rows in flight, accumulating in fp32 registers.  The groups' partial sums meet in an xor
-// butterfly and group 0 writes the D_t pooled values with one coalesced store.
+// One launch for all tables.  A wavefront takes a block of consecutive bags (bag id = t*B + b),
+// reads their offsets with one coalesced load and stages the block's indices, which are contiguous
+// in memory, in wavefront-private LDS.  The bags are then pooled G at a time, one bag per lane
+// group (LPR = pow2ceil(D/EPL) lanes x EPL-element vector loads cover a row): every group streams
+// its own bag's rows with kFwdUnroll row loads in flight, accumulates in fp32 registers and writes
+// its D_t pooled values with one coalesced store -- no cross-group reduction is needed.  Bags of one
+// batch always belong to one table, so the lane mapping is uniform inside a batch.
 template <typename WT, int EPL, int KMAX>
 __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
     const TableMeta* __restrict__ meta, const WT* __restrict__ weights,
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
-    float* __restrict__ out, int32_t B, int32_t num_bags, int32_t sumD)
+    float* __restrict__ out, int32_t B, int32_t num_bags, int32_t sumD, int32_t bags_per_wave)
 {
+    constexpr int kWaves = kFwdThreads / kWave;
+    __shared__ int32_t s_idx_all[kWaves][kFwdStage];
     const int lane = threadIdx.x & (kWave - 1);
-    const int j = uniform(blockIdx.x * (kFwdThreads / kWave) + (threadIdx.x >> 6));
-    if (j >= num_bags)
+    const int wv = threadIdx.x >> 6;
+    int32_t* s_idx = s_idx_all[wv];
+    const int j0 = uniform((blockIdx.x * kWaves + wv) * bags_per_wave);
+    if (j0 >= num_bags)
         return;
-    const int t = j / B;
-    const int b = j - t * B;
-    const TableMeta m = meta[t];
-    const int D = m.dim;
-    const int lprl = m.lpr_fwd;
-    const int LPR = 1 << lprl;
-    const int G = kWave >> lprl;
-    const int sub = lane & (LPR - 1);
-    const int grp = lane >> lprl;
-    const WT* __restrict__ wbase = weights + m.woff;
+    const int nbags = min(bags_per_wave, num_bags - j0);  // <= 63
 
-    const int64_t start = offsets[j];
-    const int L = (int)(offsets[j + 1] - start);
+    const int my_o = lane <= nbags ? (int)offsets[j0 + lane] : 0;
+    const int p_begin = __builtin_amdgcn_readlane(my_o, 0);
+    const int p_end = __shfl(my_o, nbags);
+    const int stage_n = min(p_end - p_begin, kFwdStage);
+    for (int i = lane; i < stage_n; i += kWave)
+        s_idx[i] = indices[p_begin + i];
+    __threadfence_block();
+    __builtin_amdgcn_wave_barrier();
 
-    float acc[KMAX][EPL];
+    int r = 0;
+    while (r < nbags) {
+        const int j = j0 + r;
+        const int t = j / B;
+        const TableMeta m = meta[t];
+        const int D = m.dim;
+        const int lprl = m.lpr_fwd;
+        const int LPR = 1 << lprl;
+        const int G = kWave >> lprl;
+        const int sub = lane & (LPR - 1);
+        const int grp = lane >> lprl;
+        const int same_table = (t + 1) * B - j;  // bags from j on that still belong to table t
+        const int nb = min(G, min(nbags - r, same_table));
+        const bool active = grp < nb;
+        const int rr = active ? r + grp : r;
+        // both shuffles run with every lane enabled: a bpermute cannot read a disabled lane
+        const int start = __shfl(my_o, rr);
+        const int next = __shfl(my_o, rr + 1);
+        const int len = active ? next - start : 0;
+        const WT* __restrict__ wbase = weights + m.woff;
+
+        float acc[KMAX][EPL];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k)
+        for (int k = 0; k < KMAX; ++k)
 #pragma unroll
-        for (int e = 0; e < EPL; ++e)
-            acc[k][e] = 0.f;
+            for (int e = 0; e < EPL; ++e)
+                acc[k][e] = 0.f;
 
-    for (int base = 0; base < L; base += kWave) {
-        const int n = min(kWave, L - base);
-        const int my = lane < n ? indices[start + base + lane] : 0;
-        for (int i0 = 0; i0 < n; i0 += G * kFwdUnroll) {
+        for (int it = 0; __ballot(it < len) != 0ull; it += kFwdUnroll) {
             float v[kFwdUnroll][KMAX][EPL];
 #pragma unroll
             for (int u = 0; u < kFwdUnroll; ++u) {
-                const int i = i0 + u * G + grp;
-                const int idx = __shfl(my, i & (kWave - 1));
-                const bool ok = i < n;
+                const int p = it + u;
+                const bool ok = p < len;
+                const int rel = start + p - p_begin;
+                const int idx = ok ? (rel < stage_n ? s_idx[rel] : indices[start + p]) : 0;
                 const WT* rp = wbase + (int64_t)idx * D;
 #pragma unroll
                 for (int k = 0; k < KMAX; ++k) {
@@ -175,28 +200,22 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
                     for (int e = 0; e < EPL; ++e)
                         acc[k][e] += v[u][k][e];
         }
-    }
 
-    for (int s = LPR; s < kWave; s <<= 1) {
+        if (active) {
+            const int b = j - t * B + grp;
+            float* op = out + (int64_t)b * sumD + m.col;
 #pragma unroll
-        for (int k = 0; k < KMAX; ++k)
+            for (int k = 0; k < KMAX; ++k) {
+                const int e0 = (sub + k * LPR) * EPL;
+                if (e0 < D) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e)
-                acc[k][e] += __shfl_xor(acc[k][e], s);
-    }
-
-    if (grp == 0) {
-        float* op = out + (int64_t)b * sumD + m.col;
-#pragma unroll
-        for (int k = 0; k < KMAX; ++k) {
-            const int e0 = (sub + k * LPR) * EPL;
-            if (e0 < D) {
-#pragma unroll
-                for (int q = 0; q < EPL; q += 4)
-                    *reinterpret_cast<float4*>(op + e0 + q) =
-                        make_float4(acc[k][q], acc[k][q + 1], acc[k][q + 2], acc[k][q + 3]);
+                    for (int q = 0; q < EPL; q += 4)
+                        *reinterpret_cast<float4*>(op + e0 + q) =
+                            make_float4(acc[k][q], acc[k][q + 1], acc[k][q + 2], acc[k][q + 3]);
+                }
             }
         }
+        r += nb;
     }
 }
 
