@@ -73,7 +73,7 @@ struct tbe_s {
     // workspace layout (byte offsets)
     size_t off_meta = 0, off_rowbase = 0, off_counters = 0, off_keys[2] = {0, 0}, off_vals[2] = {0, 0};
     size_t off_hist = 0, off_scan_tmp = 0, off_rl_counts = 0, off_chunk_first = 0, off_partials = 0;
-    size_t off_long_list = 0, workspace_bytes = 0;
+    size_t off_long_list = 0, off_zero = 0, workspace_bytes = 0;
     size_t weight_bytes = 0, state_bytes = 0;
 
     // bound buffers
@@ -156,6 +156,7 @@ void plan_workspace(tbe_s* h)
     h->off_meta = take(sizeof(TableMeta) * (size_t)h->T);
     h->off_rowbase = take(sizeof(uint32_t) * (size_t)(h->T + 1));
     h->off_counters = take(sizeof(Counters));
+    h->off_zero = take(kZeroRowBytes);
     const size_t nelem = (size_t)nmax + 64;  // +1 for seg_offsets' sentinel, rounded
     for (int i = 0; i < 2; ++i) {
         h->off_keys[i] = take(4 * nelem);
@@ -204,8 +205,8 @@ tbe_status_t check_call(tbe_s* h, const void* d_indices, const void* d_offsets, 
 }
 
 template <typename WT>
-tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, int32_t batch, float* out,
-                            hipStream_t st)
+tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, int32_t n_total, int32_t batch,
+                            float* out, hipStream_t st)
 {
     const int num_bags = h->T * batch;
     // bags per wavefront: enough to amortise the per-block prologue, few enough to keep >= ~16k
@@ -216,9 +217,10 @@ tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, in
     const TableMeta* meta = h->ws<TableMeta>(h->off_meta);
     const WT* w = static_cast<const WT*>(h->d_weights);
     const int sumD = (int)h->sumD;
+    const void* zero = h->ws<void>(h->off_zero);
 #define FWD(EPL, KMAX)                                                                              \
     hipLaunchKernelGGL((forward_kernel<WT, EPL, KMAX>), grid, block, 0, st, meta, w, idx, off, out, \
-                       batch, num_bags, sumD, bpw)
+                       zero, batch, num_bags, sumD, n_total, bpw)
     if constexpr (sizeof(WT) == 4) {
         if (h->fwd_kmax == 1)
             FWD(4, 1);
@@ -391,6 +393,8 @@ tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_w
     TBE_HIP_CHECK(h, hipMemcpy(h->d_ws + h->off_rowbase, rb.data(), sizeof(uint32_t) * (h->T + 1),
                                hipMemcpyHostToDevice));
     TBE_HIP_CHECK(h, hipMemcpy(h->d_ws + h->off_counters, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_zero, 0, kZeroRowBytes));
+    TBE_HIP_CHECK(h, hipDeviceSynchronize());
     h->bound = true;
     h->final_buf = -1;
     return TBE_OK;
@@ -409,8 +413,8 @@ tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t
     hipStream_t st = static_cast<hipStream_t>(stream);
     ScopedTimer tm(h, SLOT_FORWARD, st);
     if (h->dtype == TBE_DTYPE_FP32)
-        return launch_forward<float>(h, d_indices, d_offsets, batch, d_out, st);
-    return launch_forward<__half>(h, d_indices, d_offsets, batch, d_out, st);
+        return launch_forward<float>(h, d_indices, d_offsets, (int32_t)num_indices, batch, d_out, st);
+    return launch_forward<__half>(h, d_indices, d_offsets, (int32_t)num_indices, batch, d_out, st);
 }
 
 tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
@@ -509,6 +513,7 @@ tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indic
     a.moments = h->d_state;
     a.partials = h->ws<float>(h->off_partials);
     a.long_list = h->ws<uint32_t>(h->off_long_list);
+    a.zero_row = h->ws<float>(h->off_zero);
     a.n = n;
     a.num_chunks = num_chunks;
     a.T = h->T;

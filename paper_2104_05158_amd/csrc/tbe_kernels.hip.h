@@ -21,7 +21,6 @@ constexpr int kWave = 64;
 // ---- geometry constants shared by host and device ----
 constexpr int kFwdThreads = 256;          // 4 wavefronts per workgroup, each with its own block of bags
 constexpr int kFwdUnroll = 4;             // row loads in flight per lane group (8 costs occupancy and is slower)
-constexpr int kFwdStage = 512;            // indices staged in LDS per wavefront
 constexpr int kFwdMaxBagsPerWave = 8;     // measured best on configs 2-4 (4..32 tried)
 constexpr int kKeyBags = 256;             // bags per workgroup in the key build
 constexpr int kSortThreads = 512;         // 8 wavefronts
@@ -39,6 +38,7 @@ constexpr int kBwdThreads = 256;          // 4 wavefronts = 4 chunks per workgro
 constexpr int kBwdUnroll = 4;             // gradient rows in flight per lane group (long runs)
 constexpr int kShortRun = 4;              // runs up to this length are handled one per lane group
 constexpr int kMaxDim = 512;
+constexpr int kZeroRowBytes = 4096;        // a row of zeros in the workspace (largest row: 512 x fp32 = 2 KiB)
 
 struct TableMeta {      // 32 bytes, one per table, in the workspace head
     int64_t woff;       // first element of the table in the flat weight array
@@ -61,14 +61,22 @@ struct Counters {       // workspace scalars
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// Row access in the storage type: Vec is the raw vector one lane loads (EPL elements); `add`
+// converts to fp32 and accumulates.  Loads are kept raw until they are consumed so that many can
+// be in flight with few registers.
 template <typename WT, int EPL>
 struct RowIO;
 
 template <>
 struct RowIO<float, 4> {
-    __device__ static __forceinline__ void load(const float* p, float (&f)[4])
+    using Vec = float4;
+    __device__ static __forceinline__ Vec ldv(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    __device__ static __forceinline__ void add(float (&a)[4], const Vec v)
     {
-        float4 v = *reinterpret_cast<const float4*>(p);
+        a[0] += v.x; a[1] += v.y; a[2] += v.z; a[3] += v.w;
+    }
+    __device__ static __forceinline__ void unpack(const Vec v, float (&f)[4])
+    {
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
     }
     __device__ static __forceinline__ void store(float* p, const float (&f)[4])
@@ -79,12 +87,21 @@ struct RowIO<float, 4> {
 
 template <>
 struct RowIO<__half, 4> {
-    __device__ static __forceinline__ void load(const __half* p, float (&f)[4])
+    using Vec = uint2;
+    __device__ static __forceinline__ Vec ldv(const __half* p) { return *reinterpret_cast<const uint2*>(p); }
+    __device__ static __forceinline__ void unpack(Vec v, float (&f)[4])
     {
-        uint2 v = *reinterpret_cast<const uint2*>(p);
-        float2 a = __half22float2(*reinterpret_cast<__half2*>(&v.x));
-        float2 b = __half22float2(*reinterpret_cast<__half2*>(&v.y));
+        const float2 a = __half22float2(*reinterpret_cast<__half2*>(&v.x));
+        const float2 b = __half22float2(*reinterpret_cast<__half2*>(&v.y));
         f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
+    }
+    __device__ static __forceinline__ void add(float (&a)[4], const Vec v)
+    {
+        float f[4];
+        unpack(v, f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            a[e] += f[e];
     }
     __device__ static __forceinline__ void store(__half* p, const float (&f)[4])
     {
@@ -97,51 +114,52 @@ struct RowIO<__half, 4> {
 
 template <>
 struct RowIO<__half, 8> {
-    __device__ static __forceinline__ void load(const __half* p, float (&f)[8])
+    using Vec = uint4;
+    __device__ static __forceinline__ Vec ldv(const __half* p) { return *reinterpret_cast<const uint4*>(p); }
+    __device__ static __forceinline__ void add(float (&a)[8], Vec v)
     {
-        uint4 v = *reinterpret_cast<const uint4*>(p);
-        float2 a = __half22float2(*reinterpret_cast<__half2*>(&v.x));
-        float2 b = __half22float2(*reinterpret_cast<__half2*>(&v.y));
-        float2 c = __half22float2(*reinterpret_cast<__half2*>(&v.z));
-        float2 d = __half22float2(*reinterpret_cast<__half2*>(&v.w));
-        f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
-        f[4] = c.x; f[5] = c.y; f[6] = d.x; f[7] = d.y;
+        const float2 p0 = __half22float2(*reinterpret_cast<__half2*>(&v.x));
+        const float2 p1 = __half22float2(*reinterpret_cast<__half2*>(&v.y));
+        const float2 p2 = __half22float2(*reinterpret_cast<__half2*>(&v.z));
+        const float2 p3 = __half22float2(*reinterpret_cast<__half2*>(&v.w));
+        a[0] += p0.x; a[1] += p0.y; a[2] += p1.x; a[3] += p1.y;
+        a[4] += p2.x; a[5] += p2.y; a[6] += p3.x; a[7] += p3.y;
     }
 };
 
 // ---------------------------------------------------------------- forward (Section 2, Section 5.1)
 //
-// One launch for all tables.  A wavefront takes a block of consecutive bags (bag id = t*B + b),
-// reads their offsets with one coalesced load and stages the block's indices, which are contiguous
-// in memory, in wavefront-private LDS.  The bags are then pooled G at a time, one bag per lane
+// One launch for all tables.  A wavefront takes a block of consecutive bags (bag id = t*B + b) and
+// reads their offsets with one coalesced load.  The bags are pooled G at a time, one bag per lane
 // group (LPR = pow2ceil(D/EPL) lanes x EPL-element vector loads cover a row): every group streams
 // its own bag's rows with kFwdUnroll row loads in flight, accumulates in fp32 registers and writes
 // its D_t pooled values with one coalesced store -- no cross-group reduction is needed.  Bags of one
 // batch always belong to one table, so the lane mapping is uniform inside a batch.
+//
+// The inner loop is branch-free so that all loads of a step are issued back to back: slots past the
+// end of a bag read a row of zeros kept in the workspace (pointer select instead of a predicated
+// load), column offsets past D are clamped (those lanes never store), and the indices of the next
+// step are requested before the rows of the current step are consumed.
 template <typename WT, int EPL, int KMAX>
 __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
     const TableMeta* __restrict__ meta, const WT* __restrict__ weights,
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
-    float* __restrict__ out, int32_t B, int32_t num_bags, int32_t sumD, int32_t bags_per_wave)
+    float* __restrict__ out, const void* __restrict__ zero_row, int32_t B, int32_t num_bags,
+    int32_t sumD, int32_t n_total, int32_t bags_per_wave)
 {
+    using IO = RowIO<WT, EPL>;
+    using Vec = typename IO::Vec;
     constexpr int kWaves = kFwdThreads / kWave;
-    __shared__ int32_t s_idx_all[kWaves][kFwdStage];
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x >> 6;
-    int32_t* s_idx = s_idx_all[wv];
     const int j0 = uniform((blockIdx.x * kWaves + wv) * bags_per_wave);
     if (j0 >= num_bags)
         return;
     const int nbags = min(bags_per_wave, num_bags - j0);  // <= 63
 
-    const int my_o = lane <= nbags ? (int)offsets[j0 + lane] : 0;
-    const int p_begin = __builtin_amdgcn_readlane(my_o, 0);
-    const int p_end = __shfl(my_o, nbags);
-    const int stage_n = min(p_end - p_begin, kFwdStage);
-    for (int i = lane; i < stage_n; i += kWave)
-        s_idx[i] = indices[p_begin + i];
-    __threadfence_block();
-    __builtin_amdgcn_wave_barrier();
+    const int my_o = (int)offsets[j0 + min(lane, nbags)];
+    const int last = n_total - 1;
+    const WT* __restrict__ zrow = static_cast<const WT*>(zero_row);
 
     int r = 0;
     while (r < nbags) {
@@ -164,6 +182,14 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
         const int len = active ? next - start : 0;
         const WT* __restrict__ wbase = weights + m.woff;
 
+        int eoff[KMAX];
+        bool evalid[KMAX];
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const int e0 = (sub + k * LPR) * EPL;
+            evalid[k] = e0 < D;
+            eoff[k] = min(e0, D - EPL);
+        }
         float acc[KMAX][EPL];
 #pragma unroll
         for (int k = 0; k < KMAX; ++k)
@@ -171,34 +197,29 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
             for (int e = 0; e < EPL; ++e)
                 acc[k][e] = 0.f;
 
-        for (int it = 0; __ballot(it < len) != 0ull; it += kFwdUnroll) {
-            float v[kFwdUnroll][KMAX][EPL];
-#pragma unroll
-            for (int u = 0; u < kFwdUnroll; ++u) {
-                const int p = it + u;
-                const bool ok = p < len;
-                const int rel = start + p - p_begin;
-                const int idx = ok ? (rel < stage_n ? s_idx[rel] : indices[start + p]) : 0;
-                const WT* rp = wbase + (int64_t)idx * D;
-#pragma unroll
-                for (int k = 0; k < KMAX; ++k) {
-                    const int e0 = (sub + k * LPR) * EPL;
-                    if (ok && e0 < D) {
-                        RowIO<WT, EPL>::load(rp + e0, v[u][k]);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e)
-                            v[u][k][e] = 0.f;
-                    }
-                }
-            }
+        if (__ballot(len > 0) != 0ull) {
+            int idx[kFwdUnroll];
 #pragma unroll
             for (int u = 0; u < kFwdUnroll; ++u)
+                idx[u] = indices[max(0, min(start + u, last))];
+            for (int it = 0; __ballot(it < len) != 0ull; it += kFwdUnroll) {
+                Vec raw[kFwdUnroll][KMAX];
 #pragma unroll
-                for (int k = 0; k < KMAX; ++k)
+                for (int u = 0; u < kFwdUnroll; ++u) {
+                    const WT* rp = (it + u < len) ? wbase + (int64_t)idx[u] * D : zrow;
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e)
-                        acc[k][e] += v[u][k][e];
+                    for (int k = 0; k < KMAX; ++k)
+                        raw[u][k] = IO::ldv(rp + eoff[k]);
+                }
+#pragma unroll
+                for (int u = 0; u < kFwdUnroll; ++u)
+                    idx[u] = indices[max(0, min(start + it + kFwdUnroll + u, last))];
+#pragma unroll
+                for (int u = 0; u < kFwdUnroll; ++u)
+#pragma unroll
+                    for (int k = 0; k < KMAX; ++k)
+                        IO::add(acc[k], raw[u][k]);
+            }
         }
 
         if (active) {
@@ -206,11 +227,10 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
             float* op = out + (int64_t)b * sumD + m.col;
 #pragma unroll
             for (int k = 0; k < KMAX; ++k) {
-                const int e0 = (sub + k * LPR) * EPL;
-                if (e0 < D) {
+                if (evalid[k]) {
 #pragma unroll
                     for (int q = 0; q < EPL; q += 4)
-                        *reinterpret_cast<float4*>(op + e0 + q) =
+                        *reinterpret_cast<float4*>(op + eoff[k] + q) =
                             make_float4(acc[k][q], acc[k][q + 1], acc[k][q + 2], acc[k][q + 3]);
                 }
             }
@@ -645,6 +665,10 @@ __global__ __launch_bounds__(kRlThreads) void runlength_write_kernel(
 //     partials in chunk order and applies the single update.
 // Either way each touched row is read, updated and written exactly once, nothing is accumulated
 // with atomics, and the summation order is fixed: results are bit-identical run to run.
+//
+// All gathers are branch-free (slots past the end of a run read a row of zeros kept in the
+// workspace, column offsets past D are clamped) so that the loads of a step are issued back to
+// back and waited for once.
 
 __device__ __forceinline__ int find_table(const uint32_t* __restrict__ row_base, int T, uint32_t key)
 {
@@ -673,6 +697,7 @@ struct BwdArgs {
     float* moments;
     float* partials;      // [num_chunks][2][dpad]
     uint32_t* long_list;
+    const float* zero_row;  // >= 2 KiB of zeros
     int32_t n;
     int32_t num_chunks;
     int32_t T;
@@ -688,33 +713,49 @@ __device__ __forceinline__ void acc4(float (&a)[4], const float4 v)
     a[0] += v.x; a[1] += v.y; a[2] += v.z; a[3] += v.w;
 }
 
-// Whole-wavefront sum of the fp32 rows rowptr(i), i in [p0, p1).  Afterwards every lane group holds
-// the complete sums (lane `sub` of a group: elements (sub + k*LPR)*4 .. +3, k = 0, 1).
+// Per-lane column geometry of a D-float row covered by LPR lanes with two float4 blocks each.
+struct Cols {
+    int e0, e1;      // clamped element offsets of the two blocks (always loadable)
+    bool c0, c1;     // whether the block really belongs to the row
+    int sub, grp, lprl;
+    __device__ __forceinline__ Cols(int D, int lprl_, int lane) : lprl(lprl_)
+    {
+        const int LPR = 1 << lprl;
+        sub = lane & (LPR - 1);
+        grp = lane >> lprl;
+        const int a = sub * 4, b = (sub + LPR) * 4;
+        c0 = a < D;
+        c1 = b < D;
+        e0 = min(a, D - 4);
+        e1 = min(b, D - 4);
+    }
+};
+
+// Whole-wavefront sum of the fp32 rows rowptr(i), i in [p0, p1), p1 > p0; rowptr must be valid for
+// every i in the range.  Afterwards every lane group holds the complete sums.
 template <typename RowPtr>
-__device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, int D, int lprl, int lane,
-                                                float (&acc)[2][4])
+__device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, const float* __restrict__ zero_row,
+                                                const Cols& c, float (&acc)[2][4])
 {
-    const int LPR = 1 << lprl;
-    const int G = kWave >> lprl;
-    const int sub = lane & (LPR - 1);
-    const int grp = lane >> lprl;
-    const int e0 = sub * 4, e1 = (sub + LPR) * 4;
-    const bool c0 = e0 < D, c1 = e1 < D;
+    const int G = kWave >> c.lprl;
 #pragma unroll
     for (int k = 0; k < 2; ++k)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             acc[k][e] = 0.f;
-    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i0 = p0; i0 < p1; i0 += G * kBwdUnroll) {
         float4 v[kBwdUnroll][2];
+        const float* rp[kBwdUnroll];
 #pragma unroll
         for (int u = 0; u < kBwdUnroll; ++u) {
-            const int i = i0 + u * G + grp;
-            const bool ok = i < p1;
-            const float* rp = rowptr(ok ? i : p0);
-            v[u][0] = (ok && c0) ? ld4(rp + e0) : z;
-            v[u][1] = (ok && c1) ? ld4(rp + e1) : z;
+            const int i = i0 + u * G + c.grp;
+            const float* p = rowptr(min(i, p1 - 1));
+            rp[u] = i < p1 ? p : zero_row;
+        }
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u) {
+            v[u][0] = ld4(rp[u] + c.e0);
+            v[u][1] = ld4(rp[u] + c.e1);
         }
 #pragma unroll
         for (int u = 0; u < kBwdUnroll; ++u) {
@@ -722,7 +763,7 @@ __device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, i
             acc4(acc[1], v[u][1]);
         }
     }
-    for (int s = LPR; s < kWave; s <<= 1) {
+    for (int s = 1 << c.lprl; s < kWave; s <<= 1) {
 #pragma unroll
         for (int k = 0; k < 2; ++k)
 #pragma unroll
@@ -731,81 +772,101 @@ __device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, i
     }
 }
 
-// The AdaGrad epilogue for the row held by this lane's group (w: the row's old values, already loaded).
+// The AdaGrad epilogue for the row held by this lane's group (wv: the row's old values, raw).
 template <typename WT>
 __device__ __forceinline__ void adagrad_epilogue(WT* __restrict__ wrow, float* __restrict__ mptr, float m_old,
-                                                 float (&w)[2][4], const float (&acc)[2][4], int D, int lprl,
-                                                 int lane, bool writer, float lr, float eps)
+                                                 const typename RowIO<WT, 4>::Vec (&wv)[2],
+                                                 const float (&acc)[2][4], int D, const Cols& c, bool writer,
+                                                 float lr, float eps)
 {
-    const int LPR = 1 << lprl;
-    const int sub = lane & (LPR - 1);
-    const int e0 = sub * 4, e1 = (sub + LPR) * 4;
-    float ss = 0.f;
-    if (e0 < D)
-        ss += acc[0][0] * acc[0][0] + acc[0][1] * acc[0][1] + acc[0][2] * acc[0][2] + acc[0][3] * acc[0][3];
-    if (e1 < D)
-        ss += acc[1][0] * acc[1][0] + acc[1][1] * acc[1][1] + acc[1][2] * acc[1][2] + acc[1][3] * acc[1][3];
-    for (int s = 1; s < LPR; s <<= 1)
+    float ss0 = acc[0][0] * acc[0][0] + acc[0][1] * acc[0][1] + acc[0][2] * acc[0][2] + acc[0][3] * acc[0][3];
+    float ss1 = acc[1][0] * acc[1][0] + acc[1][1] * acc[1][1] + acc[1][2] * acc[1][2] + acc[1][3] * acc[1][3];
+    float ss = (c.c0 ? ss0 : 0.f) + (c.c1 ? ss1 : 0.f);
+    for (int s = 1; s < (1 << c.lprl); s <<= 1)
         ss += __shfl_xor(ss, s);
     const float m_new = m_old + ss / (float)D;
     const float scale = lr / (sqrtf(m_new) + eps);
     if (writer) {
-        if (e0 < D) {
+        float w[4];
+        if (c.c0) {
+            RowIO<WT, 4>::unpack(wv[0], w);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                w[0][e] -= scale * acc[0][e];
-            RowIO<WT, 4>::store(wrow + e0, w[0]);
+                w[e] -= scale * acc[0][e];
+            RowIO<WT, 4>::store(wrow + c.e0, w);
         }
-        if (e1 < D) {
+        if (c.c1) {
+            RowIO<WT, 4>::unpack(wv[1], w);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                w[1][e] -= scale * acc[1][e];
-            RowIO<WT, 4>::store(wrow + e1, w[1]);
+                w[e] -= scale * acc[1][e];
+            RowIO<WT, 4>::store(wrow + c.e1, w);
         }
-        if (sub == 0)
+        if (c.sub == 0)
             *mptr = m_new;
     }
 }
 
-template <typename WT>
-__device__ __forceinline__ void load_row(const WT* __restrict__ wrow, int D, int lprl, int lane, bool active,
-                                         float (&w)[2][4])
+__device__ __forceinline__ void store_partial(float* __restrict__ dst, const float (&acc)[2][4], const Cols& c)
 {
-    const int LPR = 1 << lprl;
-    const int sub = lane & (LPR - 1);
-    const int e0 = sub * 4, e1 = (sub + LPR) * 4;
+    if (c.grp == 0) {
+        if (c.c0)
+            *reinterpret_cast<float4*>(dst + c.e0) = make_float4(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+        if (c.c1)
+            *reinterpret_cast<float4*>(dst + c.e1) = make_float4(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+    }
+}
+
+// G short runs at once, one per lane group; ML = longest run of the batch (1..kShortRun).
+template <typename WT, int ML>
+__device__ __forceinline__ void short_batch(const BwdArgs& a, WT* __restrict__ wtab, const float* __restrict__ gb,
+                                            const int32_t* __restrict__ s_val, int q0, int s, int len,
+                                            uint32_t key, uint32_t rbase, int D, const Cols& c, bool active)
+{
+    using IO = RowIO<WT, 4>;
+    const int64_t sumD = a.sumD;
+    WT* wrow = wtab + (int64_t)(key - rbase) * D;          // key is a valid row even for idle groups
+    typename IO::Vec wv[2];
+    wv[0] = IO::ldv(wrow + c.e0);
+    wv[1] = IO::ldv(wrow + c.e1);
+    const float m_old = a.moments[key];
+    const float* rp[ML];
+#pragma unroll
+    for (int u = 0; u < ML; ++u) {
+        const int b = s_val[s - q0 + (u < len ? u : 0)];
+        rp[u] = (active && u < len) ? gb + (int64_t)b * sumD : a.zero_row;
+    }
+    float4 v[ML][2];
+#pragma unroll
+    for (int u = 0; u < ML; ++u) {
+        v[u][0] = ld4(rp[u] + c.e0);
+        v[u][1] = ld4(rp[u] + c.e1);
+    }
+    float acc[2][4];
 #pragma unroll
     for (int k = 0; k < 2; ++k)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            w[k][e] = 0.f;
-    if (active && e0 < D)
-        RowIO<WT, 4>::load(wrow + e0, w[0]);
-    if (active && e1 < D)
-        RowIO<WT, 4>::load(wrow + e1, w[1]);
-}
-
-__device__ __forceinline__ void store_partial(float* __restrict__ dst, const float (&acc)[2][4], int D, int lprl,
-                                              int lane)
-{
-    const int LPR = 1 << lprl;
-    const int sub = lane & (LPR - 1);
-    if ((lane >> lprl) == 0) {
-        if (sub * 4 < D)
-            *reinterpret_cast<float4*>(dst + sub * 4) = make_float4(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
-        if ((sub + LPR) * 4 < D)
-            *reinterpret_cast<float4*>(dst + (sub + LPR) * 4) =
-                make_float4(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+            acc[k][e] = 0.f;
+#pragma unroll
+    for (int u = 0; u < ML; ++u) {
+        acc4(acc[0], v[u][0]);
+        acc4(acc[1], v[u][1]);
     }
+    adagrad_epilogue<WT>(wrow, a.moments + key, m_old, wv, acc, D, c, active, a.lr, a.eps);
 }
 
 template <typename WT>
 __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
 {
+    using IO = RowIO<WT, 4>;
     constexpr int kWaves = kBwdThreads / kWave;
-    __shared__ int32_t s_seg_all[kWaves][kChunk + 2];
-    __shared__ uint32_t s_key_all[kWaves][kChunk + 1];
-    __shared__ int32_t s_val_all[kWaves][kChunk];
+    constexpr int kSegCap = 3 * kWave;             // >= kChunk + 1
+    constexpr int kValCap = kChunk + kLongRun;     // a run owned by the chunk ends within this window
+    static_assert(kChunk + 1 <= kSegCap && kChunk == 2 * kWave, "staging loops assume a 128-position chunk");
+    __shared__ int32_t s_seg_all[kWaves][kSegCap];
+    __shared__ uint32_t s_key_all[kWaves][kChunk];
+    __shared__ int32_t s_val_all[kWaves][kValCap];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x >> 6;
@@ -826,20 +887,47 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     const int32_t* __restrict__ vals = a.sorted_vals;
     const int64_t sumD = a.sumD;
 
-    // stage the chunk's run descriptors and payloads (wavefront-private LDS)
-    for (int i = lane; i <= nruns; i += kWave)
-        s_seg[i] = a.seg_offsets[ub + i];
-    for (int i = lane; i < nruns; i += kWave)
-        s_key[i] = a.unique_keys[ub + i];
-    for (int i = lane; i < q1 - q0; i += kWave)
-        s_val[i] = vals[q0 + i];
+    // ---- stage run descriptors and payloads (wavefront-private LDS); straight-line clamped loads
+    {
+        int sg[3];
+        uint32_t ky[2];
+        int vl[2];
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            sg[i] = a.seg_offsets[ub + min(i * kWave + lane, nruns)];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            ky[i] = a.unique_keys[ub + min(i * kWave + lane, max(nruns - 1, 0))];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            vl[i] = vals[min(q0 + i * kWave + lane, a.n - 1)];
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            s_seg[i * kWave + lane] = sg[i];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            s_key[i * kWave + lane] = ky[i];
+            s_val[i * kWave + lane] = vl[i];
+        }
+    }
     __threadfence_block();
     __builtin_amdgcn_wave_barrier();
+    // the last run that starts here may continue past the chunk: stage its payloads too, unless it is
+    // a long run (then only its part inside the chunk is summed here)
+    {
+        const int e_last = uniform(s_seg[nruns]);
+        const int s_last = uniform(s_seg[max(nruns - 1, 0)]);
+        if (nruns > 0 && e_last > q1 && e_last - s_last <= kLongRun) {
+            for (int p = q1 + lane; p < e_last; p += kWave)
+                s_val[p - q0] = vals[p];
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
 
     float acc[2][4];
-    float w[2][4];
     int t = -1;
-    uint32_t t_lo = 1u, t_hi = 0u;  // empty range: first key always seeks
+    uint32_t t_lo = 1u, t_hi = 0u;  // empty range: the first key always seeks
     TableMeta m;
     m.woff = 0; m.rbase = 0; m.dim = 4; m.col = 0; m.lpr_fwd = 0; m.lpr_bwd = 0; m.pad = 0;
     auto seek_table = [&](uint32_t key) {
@@ -850,7 +938,6 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
             t_hi = a.row_base[t + 1];
         }
     };
-    auto payload = [&](int p) { return p < q1 ? s_val[p - q0] : vals[p]; };
 
     // the run that is already open at q0: only its long form leaves work here
     const bool incoming = (ub >= U) || (a.seg_offsets[ub] > q0);
@@ -861,9 +948,10 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         if (e0 - s0 > kLongRun) {
             seek_table(a.unique_keys[u0]);
             const float* gb = a.grad_out + m.col;
-            wave_gather_sum([&](int i) { return gb + (int64_t)payload(i) * sumD; }, q0, min(e0, q1), m.dim,
-                            m.lpr_bwd, lane, acc);
-            store_partial(a.partials + ((int64_t)k * 2 + 0) * a.dpad, acc, m.dim, m.lpr_bwd, lane);
+            const Cols c(m.dim, m.lpr_bwd, lane);
+            wave_gather_sum([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, q0, min(e0, q1), a.zero_row,
+                            c, acc);
+            store_partial(a.partials + ((int64_t)k * 2 + 0) * a.dpad, acc, c);
         }
     }
 
@@ -877,22 +965,21 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         const int len0 = uniform(s_seg[r + 1]) - s0;
         const float* gb = a.grad_out + m.col;
         WT* wtab = weights + m.woff;
+        const Cols c(D, lprl, lane);
         if (len0 > kShortRun) {
             // ---- one run, whole wavefront
             WT* wrow = wtab + (int64_t)(key0 - m.rbase) * D;
             const bool is_long = len0 > kLongRun;
-            const bool writer = (lane >> lprl) == 0;
-            float m_old = 0.f;
-            if (!is_long) {
-                load_row<WT>(wrow, D, lprl, lane, writer, w);
-                m_old = a.moments[key0];
-            }
+            typename IO::Vec wvv[2];
+            wvv[0] = IO::ldv(wrow + c.e0);
+            wvv[1] = IO::ldv(wrow + c.e1);
+            const float m_old = a.moments[key0];
             const int e = is_long ? q1 : s0 + len0;
-            wave_gather_sum([&](int i) { return gb + (int64_t)payload(i) * sumD; }, s0, e, D, lprl, lane, acc);
+            wave_gather_sum([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, s0, e, a.zero_row, c, acc);
             if (!is_long) {
-                adagrad_epilogue<WT>(wrow, a.moments + key0, m_old, w, acc, D, lprl, lane, writer, a.lr, a.eps);
+                adagrad_epilogue<WT>(wrow, a.moments + key0, m_old, wvv, acc, D, c, c.grp == 0, a.lr, a.eps);
             } else {
-                store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, D, lprl, lane);
+                store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, c);
                 if (lane == 0) {
                     const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
                     a.long_list[slot] = (uint32_t)(ub + r);
@@ -901,45 +988,29 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
             r += 1;
         } else {
             // ---- up to G short runs of this table at once, one per lane group
-            const int LPR = 1 << lprl;
-            const int sub = lane & (LPR - 1);
-            const int grp = lane >> lprl;
-            const int rr = r + grp;
+            const int rr = r + c.grp;
             const bool in_chunk = rr < nruns;
-            const uint32_t key = in_chunk ? s_key[rr] : 0u;
-            const int s = in_chunk ? s_seg[rr] : 0;
-            const int len = in_chunk ? s_seg[rr + 1] - s : 0;
+            const int rc = in_chunk ? rr : r;  // idle groups shadow run r (loads stay valid, nothing is stored)
+            const uint32_t key = s_key[rc];
+            const int s = s_seg[rc];
+            const int len = s_seg[rc + 1] - s;
             const bool fits = in_chunk && key < t_hi && len <= kShortRun;
             const uint64_t bad = __ballot(!fits);
             const int first_bad = bad ? (int)__builtin_ctzll(bad) : kWave;
             const int nb = first_bad >> lprl;  // >= 1: run r itself fits
-            const bool active = grp < nb;
-
-            WT* wrow = wtab + (int64_t)(key - m.rbase) * D;
-            load_row<WT>(wrow, D, lprl, lane, active, w);
-            const float m_old = active ? a.moments[key] : 0.f;
-            const int e0 = sub * 4, e1 = (sub + LPR) * 4;
-            const bool c0 = e0 < D, c1 = e1 < D;
-            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-            float4 v[kShortRun][2];
-#pragma unroll
-            for (int u = 0; u < kShortRun; ++u) {
-                const bool ok = active && u < len;
-                const float* rp = gb + (int64_t)(ok ? payload(s + u) : 0) * sumD;
-                v[u][0] = (ok && c0) ? ld4(rp + e0) : z;
-                v[u][1] = (ok && c1) ? ld4(rp + e1) : z;
+            const bool active = c.grp < nb;
+            const uint32_t keyc = active ? key : key0;
+            const int sc = active ? s : s0;
+            const int lenc = active ? len : 0;
+            const int ml = 1 + (__ballot(lenc > 1) != 0ull) + (__ballot(lenc > 2) != 0ull) +
+                           (__ballot(lenc > 3) != 0ull);
+            static_assert(kShortRun == 4, "short_batch is instantiated for 1..4 lookups");
+            switch (ml) {
+                case 1: short_batch<WT, 1>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 2: short_batch<WT, 2>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 3: short_batch<WT, 3>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                default: short_batch<WT, 4>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
             }
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    acc[kk][e] = 0.f;
-#pragma unroll
-            for (int u = 0; u < kShortRun; ++u) {
-                acc4(acc[0], v[u][0]);
-                acc4(acc[1], v[u][1]);
-            }
-            adagrad_epilogue<WT>(wrow, a.moments + key, m_old, w, acc, D, lprl, lane, active, a.lr, a.eps);
             r += nb;
         }
     }
@@ -951,13 +1022,13 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
 template <typename WT>
 __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
 {
+    using IO = RowIO<WT, 4>;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave_global = uniform(blockIdx.x * (kBwdThreads / kWave) + (threadIdx.x >> 6));
     const int wave_total = gridDim.x * (kBwdThreads / kWave);
     const int cnt = (int)a.counters->long_count;
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     float acc[2][4];
-    float w[2][4];
     for (int i = wave_global; i < cnt; i += wave_total) {
         const int u = (int)a.long_list[i];
         const int s = a.seg_offsets[u];
@@ -965,17 +1036,19 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
         const uint32_t key = a.unique_keys[u];
         const int t = find_table(a.row_base, a.T, key);
         const TableMeta m = a.meta[t];
+        const Cols c(m.dim, m.lpr_bwd, lane);
         const int k0 = s / kChunk;
         const int k1 = (e - 1) / kChunk;
         const float* pbase = a.partials;
         const int64_t dpad = a.dpad;
         WT* wrow = weights + m.woff + (int64_t)(key - m.rbase) * m.dim;
-        const bool writer = (lane >> m.lpr_bwd) == 0;
-        load_row<WT>(wrow, m.dim, m.lpr_bwd, lane, writer, w);
+        typename IO::Vec wvv[2];
+        wvv[0] = IO::ldv(wrow + c.e0);
+        wvv[1] = IO::ldv(wrow + c.e1);
         const float m_old = a.moments[key];
-        wave_gather_sum([&](int c) { return pbase + ((int64_t)(k0 + c) * 2 + (c == 0 ? 1 : 0)) * dpad; }, 0,
-                        k1 - k0 + 1, m.dim, m.lpr_bwd, lane, acc);
-        adagrad_epilogue<WT>(wrow, a.moments + key, m_old, w, acc, m.dim, m.lpr_bwd, lane, writer, a.lr, a.eps);
+        wave_gather_sum([&](int cc) { return pbase + ((int64_t)(k0 + cc) * 2 + (cc == 0 ? 1 : 0)) * dpad; }, 0,
+                        k1 - k0 + 1, a.zero_row, c, acc);
+        adagrad_epilogue<WT>(wrow, a.moments + key, m_old, wvv, acc, m.dim, c, c.grp == 0, a.lr, a.eps);
     }
 }
 
