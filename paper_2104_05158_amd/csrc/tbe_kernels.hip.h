@@ -61,6 +61,9 @@ struct Counters {       // workspace scalars
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// fp16 -> fp32 accumulate as one mixed-precision FMA: x*1 + a is exactly a + x
+__device__ __forceinline__ float acc_half(float a, __half h) { return __builtin_fmaf(__half2float(h), 1.0f, a); }
+
 // Row access in the storage type: Vec is the raw vector one lane loads (EPL elements); `add`
 // converts to fp32 and accumulates.  Loads are kept raw until they are consumed so that many can
 // be in flight with few registers.
@@ -95,13 +98,12 @@ struct RowIO<__half, 4> {
         const float2 b = __half22float2(*reinterpret_cast<__half2*>(&v.y));
         f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
     }
-    __device__ static __forceinline__ void add(float (&a)[4], const Vec v)
+    __device__ static __forceinline__ void add(float (&a)[4], Vec v)
     {
-        float f[4];
-        unpack(v, f);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            a[e] += f[e];
+        const __half2 x = *reinterpret_cast<__half2*>(&v.x);
+        const __half2 y = *reinterpret_cast<__half2*>(&v.y);
+        a[0] = acc_half(a[0], __low2half(x)); a[1] = acc_half(a[1], __high2half(x));
+        a[2] = acc_half(a[2], __low2half(y)); a[3] = acc_half(a[3], __high2half(y));
     }
     __device__ static __forceinline__ void store(__half* p, const float (&f)[4])
     {
@@ -118,12 +120,14 @@ struct RowIO<__half, 8> {
     __device__ static __forceinline__ Vec ldv(const __half* p) { return *reinterpret_cast<const uint4*>(p); }
     __device__ static __forceinline__ void add(float (&a)[8], Vec v)
     {
-        const float2 p0 = __half22float2(*reinterpret_cast<__half2*>(&v.x));
-        const float2 p1 = __half22float2(*reinterpret_cast<__half2*>(&v.y));
-        const float2 p2 = __half22float2(*reinterpret_cast<__half2*>(&v.z));
-        const float2 p3 = __half22float2(*reinterpret_cast<__half2*>(&v.w));
-        a[0] += p0.x; a[1] += p0.y; a[2] += p1.x; a[3] += p1.y;
-        a[4] += p2.x; a[5] += p2.y; a[6] += p3.x; a[7] += p3.y;
+        const __half2 x = *reinterpret_cast<__half2*>(&v.x);
+        const __half2 y = *reinterpret_cast<__half2*>(&v.y);
+        const __half2 z = *reinterpret_cast<__half2*>(&v.z);
+        const __half2 w = *reinterpret_cast<__half2*>(&v.w);
+        a[0] = acc_half(a[0], __low2half(x)); a[1] = acc_half(a[1], __high2half(x));
+        a[2] = acc_half(a[2], __low2half(y)); a[3] = acc_half(a[3], __high2half(y));
+        a[4] = acc_half(a[4], __low2half(z)); a[5] = acc_half(a[5], __high2half(z));
+        a[6] = acc_half(a[6], __low2half(w)); a[7] = acc_half(a[7], __high2half(w));
     }
 };
 
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
     const int nbags = min(bags_per_wave, num_bags - j0);  // <= 63
 
     const int my_o = (int)offsets[j0 + min(lane, nbags)];
-    const int last = n_total - 1;
+    const uint32_t last = (uint32_t)(n_total - 1);
     const WT* __restrict__ zrow = static_cast<const WT*>(zero_row);
 
     int r = 0;
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
             int idx[kFwdUnroll];
 #pragma unroll
             for (int u = 0; u < kFwdUnroll; ++u)
-                idx[u] = indices[max(0, min(start + u, last))];
+                idx[u] = indices[min((uint32_t)(start + u), last)];
             for (int it = 0; __ballot(it < len) != 0ull; it += kFwdUnroll) {
                 Vec raw[kFwdUnroll][KMAX];
 #pragma unroll
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
                 }
 #pragma unroll
                 for (int u = 0; u < kFwdUnroll; ++u)
-                    idx[u] = indices[max(0, min(start + it + kFwdUnroll + u, last))];
+                    idx[u] = indices[min((uint32_t)(start + it + kFwdUnroll + u), last)];
 #pragma unroll
                 for (int u = 0; u < kFwdUnroll; ++u)
 #pragma unroll
@@ -310,11 +314,16 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     volatile uint32_t* wh = s_hist[wave];
     const int base = blockIdx.x * kSortTile + wave * (kSortTile / (kSortThreads / kWave));
     const uint64_t lt = (1ull << lane) - 1ull;
-#pragma unroll 4
+    // all 16 key loads are issued before the first one is used (positions past n are clamped)
+    uint32_t key[kSortKeysPerThread];
+#pragma unroll
+    for (int r = 0; r < kSortKeysPerThread; ++r)
+        key[r] = keys[min(base + r * kWave + lane, n - 1)];
+#pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
         const int q = base + r * kWave + lane;
         const bool valid = q < n;
-        const uint32_t dg = valid ? ((keys[q] >> shift) & mask) : 0u;
+        const uint32_t dg = (key[r] >> shift) & mask;
         const uint64_t peers = match_digit(dg, valid, bits);
         if (valid && (peers & lt) == 0)
             wh[dg] = wh[dg] + (uint32_t)__popcll(peers);
@@ -360,9 +369,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
         const int q = base + r * kWave + lane;
-        const bool valid = q < n;
-        key[r] = valid ? keys_in[q] : 0xffffffffu;
-        val[r] = valid ? vals_in[q] : 0;
+        key[r] = keys_in[min(q, n - 1)];
+        val[r] = vals_in[min(q, n - 1)];
     }
     volatile uint32_t* wh = s_whist[wave];
     const uint64_t lt = (1ull << lane) - 1ull;
@@ -784,8 +792,9 @@ __device__ __forceinline__ void adagrad_epilogue(WT* __restrict__ wrow, float* _
     float ss = (c.c0 ? ss0 : 0.f) + (c.c1 ? ss1 : 0.f);
     for (int s = 1; s < (1 << c.lprl); s <<= 1)
         ss += __shfl_xor(ss, s);
-    const float m_new = m_old + ss / (float)D;
-    const float scale = lr / (sqrtf(m_new) + eps);
+    // hardware reciprocal / square root (1 ulp each): far inside the 1e-5 tolerance of the result
+    const float m_new = m_old + ss * __builtin_amdgcn_rcpf((float)D);
+    const float scale = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(m_new) + eps);
     if (writer) {
         float w[4];
         if (c.c0) {
