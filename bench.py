@@ -45,6 +45,9 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for HBM counter scaling)")
     ap.add_argument("--fwd-only", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the backward's sort (it needs only the indices) on a second stream beside the "
+                         "forward gather; measured: no gain, both kernels fill the chip on their own")
     return ap.parse_args()
 
 
@@ -171,10 +174,22 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
+    overlap = args.overlap and not args.fwd_only
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream() if overlap else None
+
     def step(i):
         b = batches[i % len(batches)]
         if flush_buf is not None:
             flush_buf.fill_(i & 0xFF)
+        if overlap:
+            # a2-a4 (keys, sort, run-length) depend only on the indices: they run beside the forward
+            side_stream.wait_stream(main_stream)
+            op.backward_sort(b.indices, b.offsets, spec.batch, stream=side_stream, num_indices=b.num_indices)
+            op.forward(b.indices, b.offsets, spec.batch, out=out, num_indices=b.num_indices)
+            main_stream.wait_stream(side_stream)
+            op.backward_update_rowwise_adagrad(grad, spec.lr, spec.eps)
+            return
         op.forward(b.indices, b.offsets, spec.batch, out=out, num_indices=b.num_indices)
         if not args.fwd_only:
             op.backward_rowwise_adagrad(b.indices, b.offsets, spec.batch, grad, spec.lr, spec.eps,
@@ -271,6 +286,7 @@ def main():
             "index_dist": spec.index_dist if spec.index_dist == "uniform" else f"zipf({spec.zipf_s})",
             "rotation": len(batches),
             "cache_flush": bool(args.flush),
+            "streams": 2 if overlap else 1,
         },
         "roofline": roofline,
         "kernels": kernels,

@@ -140,6 +140,22 @@ TBE_API tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t*
                                           float eps, void* stream);
 
 /*
+ * The same backward pass in two calls, for callers that overlap work (Section 4.2 pipelines
+ * independent stages on separate streams).  tbe_backward_sort enqueues the part that needs only the
+ * batch's (indices, offsets): key build, radix sort, run-length segmentation (Section 5.1 "gradient
+ * sorting by rows"); it may run on another stream, concurrently with tbe_forward or with dense
+ * layers.  tbe_backward_update_rowwise_adagrad enqueues the aggregation + optimizer step
+ * (Sections 5.1, 5.2) for the batch sorted last; the caller must order it after that sort (same
+ * stream, or an event) and must not start the next sort of this handle before it has finished:
+ * both use the handle's workspace.  tbe_backward_rowwise_adagrad is exactly these two in a row.
+ * Errors: as tbe_forward; update without a preceding sort returns INVALID_ARG.
+ */
+TBE_API tbe_status_t tbe_backward_sort(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                                       int64_t num_indices, int32_t batch, void* stream);
+TBE_API tbe_status_t tbe_backward_update_rowwise_adagrad(tbe_handle_t h, const float* d_grad_out, float lr,
+                                                         float eps, void* stream);
+
+/*
  * Device pointers (into the workspace) of the last backward call's integer artefacts
  * (Section 5.1 "gradient sorting by rows"), valid once that call's stream work has completed:
  *   d_sorted_keys  uint32[num_indices]  linear row ids, ascending

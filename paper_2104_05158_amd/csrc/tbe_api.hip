@@ -82,6 +82,7 @@ struct tbe_s {
     char* d_ws = nullptr;
     bool bound = false;
     int final_buf = -1;  // which (keys, vals) pair holds the sorted result of the last backward
+    int32_t sorted_n = -1, sorted_batch = 0;  // size of the batch that was sorted last
 
     // profiling
     std::vector<hipEvent_t> ev_pool;
@@ -397,6 +398,7 @@ tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_w
     TBE_HIP_CHECK(h, hipDeviceSynchronize());
     h->bound = true;
     h->final_buf = -1;
+    h->sorted_n = -1;
     return TBE_OK;
 }
 
@@ -417,25 +419,20 @@ tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t
     return launch_forward<__half>(h, d_indices, d_offsets, (int32_t)num_indices, batch, d_out, st);
 }
 
-tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
-                                          const int64_t* d_offsets, int64_t num_indices, int32_t batch,
-                                          const float* d_grad_out, float lr, float eps, void* stream)
+// a2..a4: needs only the batch's (indices, offsets)
+static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64_t* d_offsets, int32_t n,
+                                 int32_t batch, hipStream_t st)
 {
-    tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
-    if (rc != TBE_OK)
-        return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    tbe_status_t rc = TBE_OK;
     Counters* counters = h->ws<Counters>(h->off_counters);
-    const int32_t n = (int32_t)num_indices;
+    h->sorted_n = n;
+    h->sorted_batch = batch;
     if (batch == 0 || n == 0) {
         hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(1), 0, st, counters);
         TBE_LAUNCH_CHECK(h, "clear_counters_kernel");
         h->final_buf = 0;
         return TBE_OK;
     }
-    if (!d_grad_out)
-        return TBE_ERR_INVALID_ARG;
-
     const int num_bags = h->T * batch;
     const uint32_t* row_base = h->ws<uint32_t>(h->off_rowbase);
     uint32_t* keys[2] = {h->ws<uint32_t>(h->off_keys[0]), h->ws<uint32_t>(h->off_keys[1])};
@@ -498,6 +495,26 @@ tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indic
         TBE_LAUNCH_CHECK(h, "runlength kernels");
     }
 
+    return TBE_OK;
+}
+
+// a5 + a6 on the artefacts left by enqueue_sort
+static tbe_status_t enqueue_update(tbe_s* h, const float* d_grad_out, float lr, float eps, hipStream_t st)
+{
+    const int32_t n = h->sorted_n;
+    if (h->sorted_batch == 0 || n == 0)
+        return TBE_OK;
+    if (!d_grad_out)
+        return TBE_ERR_INVALID_ARG;
+    const int cur = h->final_buf;
+    Counters* counters = h->ws<Counters>(h->off_counters);
+    const uint32_t* row_base = h->ws<uint32_t>(h->off_rowbase);
+    uint32_t* keys[2] = {h->ws<uint32_t>(h->off_keys[0]), h->ws<uint32_t>(h->off_keys[1])};
+    int32_t* vals[2] = {h->ws<int32_t>(h->off_vals[0]), h->ws<int32_t>(h->off_vals[1])};
+    uint32_t* unique_keys = keys[cur ^ 1];
+    int32_t* seg_offsets = vals[cur ^ 1];
+    int32_t* chunk_first = h->ws<int32_t>(h->off_chunk_first);
+    const int num_chunks = (int)ceil_div(n, kChunk);
     // a5 + a6: on-chip aggregation per run, one AdaGrad step per touched row
     BwdArgs a;
     a.meta = h->ws<TableMeta>(h->off_meta);
@@ -542,6 +559,43 @@ tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indic
         TBE_LAUNCH_CHECK(h, "long_run_fixup_kernel");
     }
     return TBE_OK;
+}
+
+tbe_status_t tbe_backward_sort(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                               int64_t num_indices, int32_t batch, void* stream)
+{
+    tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
+    if (rc != TBE_OK)
+        return rc;
+    return enqueue_sort(h, d_indices, d_offsets, (int32_t)num_indices, batch, static_cast<hipStream_t>(stream));
+}
+
+tbe_status_t tbe_backward_update_rowwise_adagrad(tbe_handle_t h, const float* d_grad_out, float lr, float eps,
+                                                 void* stream)
+{
+    if (!h)
+        return TBE_ERR_INVALID_ARG;
+    if (!h->bound)
+        return TBE_ERR_NOT_BOUND;
+    if (h->final_buf < 0 || h->sorted_n < 0)
+        return TBE_ERR_INVALID_ARG;
+    return enqueue_update(h, d_grad_out, lr, eps, static_cast<hipStream_t>(stream));
+}
+
+tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
+                                          const int64_t* d_offsets, int64_t num_indices, int32_t batch,
+                                          const float* d_grad_out, float lr, float eps, void* stream)
+{
+    tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
+    if (rc != TBE_OK)
+        return rc;
+    if (batch > 0 && num_indices > 0 && !d_grad_out)
+        return TBE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = enqueue_sort(h, d_indices, d_offsets, (int32_t)num_indices, batch, st);
+    if (rc != TBE_OK)
+        return rc;
+    return enqueue_update(h, d_grad_out, lr, eps, st);
 }
 
 tbe_status_t tbe_backward_artifacts(tbe_handle_t h, const uint32_t** d_sorted_keys,

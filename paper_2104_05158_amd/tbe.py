@@ -29,7 +29,8 @@ TBE_POOLING_SUM = 0
 
 EXPORTED = [
     "tbe_create", "tbe_destroy", "tbe_query_sizes", "tbe_bind", "tbe_forward",
-    "tbe_backward_rowwise_adagrad", "tbe_backward_artifacts", "tbe_check_inputs",
+    "tbe_backward_rowwise_adagrad", "tbe_backward_sort", "tbe_backward_update_rowwise_adagrad",
+    "tbe_backward_artifacts", "tbe_check_inputs",
     "tbe_profile_enable", "tbe_profile_read", "tbe_status_string", "tbe_last_hip_error",
 ]
 
@@ -70,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.tbe_bind.argtypes = [vp, vp, vp, vp, ctypes.c_size_t]
         L.tbe_forward.argtypes = [vp, vp, vp, i64, i32, vp, vp]
         L.tbe_backward_rowwise_adagrad.argtypes = [vp, vp, vp, i64, i32, vp, f32, f32, vp]
+        L.tbe_backward_sort.argtypes = [vp, vp, vp, i64, i32, vp]
+        L.tbe_backward_update_rowwise_adagrad.argtypes = [vp, vp, f32, f32, vp]
         L.tbe_backward_artifacts.argtypes = [vp] + [ctypes.POINTER(vp)] * 5
         L.tbe_check_inputs.argtypes = [vp, vp, vp, i64, i32, vp]
         L.tbe_profile_enable.argtypes = [vp, i32]
@@ -143,6 +146,16 @@ def tbe_backward_rowwise_adagrad(h, indices, offsets, num_indices: int, batch: i
                                  eps: float, stream=None) -> int:
     return lib().tbe_backward_rowwise_adagrad(ctypes.c_void_p(h), _ptr(indices), _ptr(offsets), num_indices,
                                               batch, _ptr(grad_out), lr, eps, _stream_ptr(stream))
+
+
+def tbe_backward_sort(h, indices, offsets, num_indices: int, batch: int, stream=None) -> int:
+    return lib().tbe_backward_sort(ctypes.c_void_p(h), _ptr(indices), _ptr(offsets), num_indices, batch,
+                                   _stream_ptr(stream))
+
+
+def tbe_backward_update_rowwise_adagrad(h, grad_out, lr: float, eps: float, stream=None) -> int:
+    return lib().tbe_backward_update_rowwise_adagrad(ctypes.c_void_p(h), _ptr(grad_out), lr, eps,
+                                                     _stream_ptr(stream))
 
 
 def tbe_backward_artifacts(h):
@@ -245,6 +258,18 @@ class TableBatchedEmbeddingBags:
         rc = tbe_backward_rowwise_adagrad(self.h, indices, offsets, n, batch, grad_out, lr, eps, stream)
         if rc != TBE_OK:
             raise TbeError(rc, "tbe_backward_rowwise_adagrad", tbe_last_hip_error(self.h))
+
+    def backward_sort(self, indices, offsets, batch: int, stream=None, num_indices: Optional[int] = None):
+        n = indices.numel() if num_indices is None else num_indices
+        self._last_n = n
+        rc = tbe_backward_sort(self.h, indices, offsets, n, batch, stream)
+        if rc != TBE_OK:
+            raise TbeError(rc, "tbe_backward_sort", tbe_last_hip_error(self.h))
+
+    def backward_update_rowwise_adagrad(self, grad_out, lr: float, eps: float, stream=None):
+        rc = tbe_backward_update_rowwise_adagrad(self.h, grad_out, lr, eps, stream)
+        if rc != TBE_OK:
+            raise TbeError(rc, "tbe_backward_update_rowwise_adagrad", tbe_last_hip_error(self.h))
 
     def check_inputs(self, indices, offsets, batch: int, num_indices: Optional[int] = None) -> int:
         n = indices.numel() if num_indices is None else num_indices

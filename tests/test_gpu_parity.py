@@ -169,6 +169,38 @@ def test_backward_is_deterministic_run_to_run(gpu_device):
         assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
 
 
+def test_split_backward_on_two_streams_matches_single_call(gpu_device):
+    # sort on a side stream while forward runs on the main one, then the update: same bits as one call
+    spec = wl.custom([3000, 200, 40_000], [128, 32, 64], 1, 400, [25.0, 6.0, 12.0], index_dist="zipf", name="split")
+    idx, off, w, g = _np_case(spec, 47)
+    a = [torch.from_numpy(x).to(gpu_device) for x in (idx, off, g)]
+    ref = tl.make_op(spec, gpu_device, max_indices=len(idx), weights=torch.from_numpy(w.copy()).to(gpu_device))
+    out_ref = ref.forward(a[0], a[1], spec.batch)
+    ref.backward_rowwise_adagrad(a[0], a[1], spec.batch, a[2], 0.01, 1e-8)
+    op = tl.make_op(spec, gpu_device, max_indices=len(idx), weights=torch.from_numpy(w.copy()).to(gpu_device))
+    assert tbe.tbe_backward_update_rowwise_adagrad(op.h, a[2], 0.01, 1e-8) == tbe.TBE_ERR_INVALID_ARG  # no sort yet
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    for _ in range(3):      # repeated use of the same workspace must stay ordered by the caller's events
+        side.wait_stream(main)
+        op.backward_sort(a[0], a[1], spec.batch, stream=side)
+        out = op.forward(a[0], a[1], spec.batch)
+        main.wait_stream(side)
+        op.backward_update_rowwise_adagrad(a[2], 0.0, 1e-8)          # lr 0: weights keep their bits
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_ref)
+    op.state.zero_()
+    side.wait_stream(main)
+    op.backward_sort(a[0], a[1], spec.batch, stream=side)
+    main.wait_stream(side)
+    op.backward_update_rowwise_adagrad(a[2], 0.01, 1e-8)
+    torch.cuda.synchronize()
+    assert torch.equal(op.weights, ref.weights) and torch.equal(op.state, ref.state)
+    ar, ao = ref.artifacts(), op.artifacts()
+    for k in ("sorted_keys", "sorted_vals", "unique_keys", "seg_offsets"):
+        assert torch.equal(ar[k], ao[k])
+
+
 def test_two_steps_carry_moments(gpu_device):
     # second step starts from the first step's weights and moments (Section 5.2: the moment accumulates)
     spec = wl.custom([500, 60], [64, 16], 0, 64, [12.0, 5.0], index_dist="zipf", name="two")
