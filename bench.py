@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--rotation", type=int, default=4, help="number of pre-generated batches")
     ap.add_argument("--flush", action="store_true", help="write a 1 GiB scratch between steps (cold caches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-lookups", type=float, default=4e6)
+    ap.add_argument("--cpu-sample-lookups", type=float, default=8e6)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for HBM counter scaling)")
     ap.add_argument("--fwd-only", action="store_true")
@@ -250,14 +250,14 @@ def main():
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "algorithmic_bytes_per_launch": kb[dominant], "ms_per_launch": dom_ms}
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    # measured L2<->fabric bytes per launch of that kernel (two rocprofv3 --pmc runs, summarised in profiles/)
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(traffic_file):
-        try:
-            tr = json.load(open(traffic_file)).get(spec.name, {}).get(dominant)
-            if tr is not None:
-                roofline["traffic"] = tr
-        except Exception:
-            pass
+        for line in open(traffic_file):
+            f = line.split()
+            if len(f) == 3 and f[0] == spec.name and f[1] == dominant + "_kernel":
+                roofline["traffic"] = float(f[2])
+                roofline["traffic_GBps"] = round(float(f[2]) / (dom_ms * 1e-3) / 1e9, 1)
 
     ms_per_step = elapsed / args.steps * 1e3
     fwd_ms = kernels.get("forward", {}).get("ms_per_step", 0.0)
