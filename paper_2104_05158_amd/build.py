@@ -11,8 +11,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtbe.so")
-SOURCES = [os.path.join(CSRC, "tbe_api.hip")]
-HEADERS = [os.path.join(CSRC, "tbe_kernels.hip.h"), os.path.join(ROOT, "include", "tbe.h")]
+SOURCES = [os.path.join(CSRC, "tbe_api.hip"), os.path.join(CSRC, "tbe_inputs_api.hip")]
+HEADERS = [os.path.join(CSRC, "tbe_kernels.hip.h"), os.path.join(CSRC, "tbe_inputs_kernels.hip.h"),
+           os.path.join(ROOT, "include", "tbe.h"), os.path.join(ROOT, "include", "tbe_inputs.h")]
 
 # packed fp32 ALU ops are switched off for all device code of this library
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fvisibility=hidden",

@@ -33,6 +33,10 @@ EXPORTED = [
     "tbe_backward_artifacts", "tbe_check_inputs",
     "tbe_profile_enable", "tbe_profile_read", "tbe_status_string", "tbe_last_hip_error",
 ]
+# include/tbe_inputs.h
+EXPORTED_INPUTS = [
+    "tbe_inputs_scratch_bytes", "tbe_lengths_to_offsets", "tbe_permute_wtb_to_twb", "tbe_bucketize_rowwise",
+]
 
 
 class TbeError(RuntimeError):
@@ -78,8 +82,14 @@ def lib() -> ctypes.CDLL:
         L.tbe_profile_enable.argtypes = [vp, i32]
         L.tbe_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64),
                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
-        for name in EXPORTED:
+        sz = ctypes.c_size_t
+        L.tbe_inputs_scratch_bytes.argtypes = [i64]
+        L.tbe_lengths_to_offsets.argtypes = [vp, i64, vp, vp, sz, vp]
+        L.tbe_permute_wtb_to_twb.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+        L.tbe_bucketize_rowwise.argtypes = [i32, i32, i32, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+        for name in EXPORTED + EXPORTED_INPUTS:
             getattr(L, name).restype = ctypes.c_int
+        L.tbe_inputs_scratch_bytes.restype = sz
         L.tbe_status_string.argtypes = [ctypes.c_int]
         L.tbe_status_string.restype = ctypes.c_char_p
         L.tbe_last_hip_error.argtypes = [vp]
@@ -189,6 +199,35 @@ def tbe_profile_read(h) -> Tuple[int, Dict[str, Tuple[int, float]]]:
 
 def tbe_last_hip_error(h) -> str:
     return lib().tbe_last_hip_error(ctypes.c_void_p(h)).decode()
+
+
+# ---- input-side entry points (include/tbe_inputs.h); the caller provides every buffer ----
+
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def tbe_inputs_scratch_bytes(num_bags: int) -> int:
+    return int(lib().tbe_inputs_scratch_bytes(num_bags))
+
+
+def tbe_lengths_to_offsets(lengths, num_bags: int, offsets, scratch, stream=None) -> int:
+    return lib().tbe_lengths_to_offsets(_ptr(lengths), num_bags, _ptr(offsets), _ptr(scratch), _nbytes(scratch),
+                                        _stream_ptr(stream))
+
+
+def tbe_permute_wtb_to_twb(W: int, T: int, B: int, lengths_in, indices_in, num_indices: int, lengths_out,
+                           offsets_out, indices_out, scratch, stream=None) -> int:
+    return lib().tbe_permute_wtb_to_twb(W, T, B, _ptr(lengths_in), _ptr(indices_in), num_indices,
+                                        _ptr(lengths_out), _ptr(offsets_out), _ptr(indices_out), _ptr(scratch),
+                                        _nbytes(scratch), _stream_ptr(stream))
+
+
+def tbe_bucketize_rowwise(T: int, B: int, W: int, rows, indices, offsets, num_indices: int, lengths_out,
+                          offsets_out, indices_out, scratch, stream=None) -> int:
+    return lib().tbe_bucketize_rowwise(T, B, W, _ptr(rows), _ptr(indices), _ptr(offsets), num_indices,
+                                       _ptr(lengths_out), _ptr(offsets_out), _ptr(indices_out), _ptr(scratch),
+                                       _nbytes(scratch), _stream_ptr(stream))
 
 
 def _view_device(ptr: int, nbytes: int, dtype: torch.dtype, owner: torch.Tensor) -> torch.Tensor:

@@ -230,3 +230,25 @@ def tiny_random(seed: int, T: int = 3, max_rows: int = 16, dims=(4, 8), B: int =
     weights = rng.uniform(-1, 1, size=spec.weight_elems).astype(wdt)
     grad = rng.normal(size=(B, spec.sumD)).astype(np.float32)
     return spec, indices, offsets, weights, grad
+
+
+def make_wtb_input(W: int, T: int, B: int, rows, pooling_mean: float, device="cpu", seed: int = 0,
+                   max_len: Optional[int] = None):
+    """Combined-format input as it arrives after the all-to-alls of table-wise sharding (Section 7.1):
+    int32 lengths of the W*T*B bags in (W, T, B) order and their concatenated int32 indices (uniform
+    rows of the bag's table).  `max_len` draws lengths uniformly in [0, max_len] instead of Poisson."""
+    device = torch.device(device)
+    g = _gen(device, BASE_SEED + 31 * seed + 5)
+    n = W * T * B
+    if max_len is None:
+        lens = torch.poisson(torch.full((n,), float(pooling_mean), device=device), generator=g).to(torch.int32)
+    else:
+        lens = torch.randint(0, max_len + 1, (n,), generator=g, device=device, dtype=torch.int32)
+    total = int(lens.sum().item())
+    H = torch.as_tensor(np.asarray(rows, np.int64), device=device)
+    bag_table = torch.arange(T, device=device).repeat_interleave(B).repeat(W)           # table of bag (w,t,b)
+    pos_table = bag_table.repeat_interleave(lens.to(torch.int64), output_size=total)
+    u = torch.rand(total, generator=g, device=device, dtype=torch.float64)
+    indices = (u * H[pos_table].to(torch.float64)).floor().to(torch.int64)
+    indices = torch.minimum(indices, H[pos_table] - 1).to(torch.int32)
+    return lens, indices

@@ -13,8 +13,8 @@ from paper_2104_05158_amd import tbe
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "tbe.h")).read()
+def _declared_symbols(header="tbe.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tbe_[a-z_]+)\s*\(", text)))
 
@@ -23,6 +23,10 @@ def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
     assert set(names) == set(tbe.EXPORTED)
     L = ctypes.CDLL(tbe.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    names = _declared_symbols("tbe_inputs.h")
+    assert set(names) == set(tbe.EXPORTED_INPUTS)
     for n in names:
         assert hasattr(L, n), n
 
@@ -92,3 +96,36 @@ def test_calls_on_unbound_or_null_handles():
     assert L.tbe_query_sizes(None, None, None, None, None, None, None) == tbe.TBE_ERR_INVALID_ARG
     assert tbe.tbe_last_hip_error(h) == ""
     tbe.tbe_destroy(h)
+
+
+def test_input_side_entry_points_validate_on_the_host():
+    """Every error below is detected before anything is enqueued (there is no GPU here)."""
+    L = tbe.lib()
+    assert tbe.tbe_inputs_scratch_bytes(0) >= 16 and tbe.tbe_inputs_scratch_bytes(0) % 256 == 0
+    n = 10 ** 6
+    need = tbe.tbe_inputs_scratch_bytes(n)
+    assert 8 * (n + 1) <= need <= 8 * (n + 1) + 8 * (n // 4096 + 2) + 512
+    fake = 0x10000  # an aligned non-null address that is never dereferenced on these paths
+    bad = tbe.TBE_ERR_INVALID_ARG
+    # lengths -> offsets
+    assert L.tbe_lengths_to_offsets(fake, -1, fake, fake, need, None) == bad
+    assert L.tbe_lengths_to_offsets(None, 5, fake, fake, need, None) == bad
+    assert L.tbe_lengths_to_offsets(fake, 5, None, fake, need, None) == bad
+    assert L.tbe_lengths_to_offsets(fake, 5, fake, None, need, None) == bad
+    assert L.tbe_lengths_to_offsets(fake, n, fake, fake, need - 1, None) == bad          # scratch too small
+    assert L.tbe_lengths_to_offsets(fake, 5, fake, fake + 8, need, None) == bad          # scratch misaligned
+    assert L.tbe_lengths_to_offsets(fake + 4, 5, fake, fake, need, None) == bad          # lengths misaligned
+    assert L.tbe_lengths_to_offsets(fake, 2 ** 31, fake, fake, 2 ** 40, None) == tbe.TBE_ERR_UNSUPPORTED
+    # permute
+    assert L.tbe_permute_wtb_to_twb(0, 1, 1, fake, fake, 1, fake, fake, fake, fake, need, None) == bad
+    assert L.tbe_permute_wtb_to_twb(2, 2, 2, None, fake, 1, fake, fake, fake, fake, need, None) == bad
+    assert L.tbe_permute_wtb_to_twb(2, 2, 2, fake, None, 1, fake, fake, fake, fake, need, None) == bad
+    assert L.tbe_permute_wtb_to_twb(2, 2, 2, fake, fake, 1, fake, fake, fake, fake, 8, None) == bad
+    assert L.tbe_permute_wtb_to_twb(2 ** 11, 2 ** 10, 2 ** 10, fake, fake, 1, fake, fake, fake, fake, 2 ** 40,
+                                    None) == tbe.TBE_ERR_UNSUPPORTED
+    # bucketize
+    assert L.tbe_bucketize_rowwise(1, 4, 0, fake, fake, fake, 1, fake, fake, fake, fake, need, None) == bad
+    assert L.tbe_bucketize_rowwise(1, 4, 2, None, fake, fake, 1, fake, fake, fake, fake, need, None) == bad
+    assert L.tbe_bucketize_rowwise(1, 4, 2, fake, fake, fake, 1, fake, fake, fake, fake, 8, None) == bad
+    assert L.tbe_bucketize_rowwise(1, 4, 1025, fake, fake, fake, 1, fake, fake, fake, fake, 2 ** 40,
+                                   None) == tbe.TBE_ERR_UNSUPPORTED
