@@ -45,6 +45,10 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for HBM counter scaling)")
     ap.add_argument("--fwd-only", action="store_true")
+    ap.add_argument("--inputs", action="store_true",
+                    help="time the input-side kernels (row-wise bucketize, (W,T,B)->(T,W,B) permute, lengths->offsets) "
+                         "on the chosen config's batch instead of the embedding step")
+    ap.add_argument("--shards", type=int, default=8, help="W for --inputs")
     ap.add_argument("--overlap", action="store_true",
                     help="run the backward's sort (it needs only the indices) on a second stream beside the "
                          "forward gather; measured: no gain, both kernels fill the chip on their own")
@@ -140,6 +144,56 @@ def cpu_baseline(spec, batch, weights, grad, target_lookups):
     }
 
 
+def bench_inputs(args, spec, dev):
+    """Section 7.1 / Section 4 input-side kernels on one batch of `spec`: bucketize over W shards, permute of
+    the bucketized (W,T,B) result to (T,W,B), and lengths -> offsets of its W*T*B lengths."""
+    import torch
+
+    from paper_2104_05158_amd import tbe
+    from paper_2104_05158_amd import workloads as wl
+
+    W, T, B = args.shards, spec.T, spec.batch
+    b = wl.make_batch(spec, dev, it=0)
+    N, n_in, n_out = b.num_indices, T * B, W * T * B
+    rows = torch.from_numpy(spec.rows).to(dev)
+    scratch = torch.empty(tbe.tbe_inputs_scratch_bytes(n_out), dtype=torch.uint8, device=dev)
+    i32 = lambda n: torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    i64 = lambda n: torch.empty(n, dtype=torch.int64, device=dev)
+    len_b, off_b, idx_b = i32(n_out), i64(n_out + 1), i32(N)
+    len_p, off_p, idx_p = i32(n_out), i64(n_out + 1), i32(N)
+    off_l = i64(n_out + 1)
+    calls = {
+        "bucketize_rowwise": (lambda: tbe.tbe_bucketize_rowwise(T, B, W, rows, b.indices, b.offsets, N, len_b, off_b,
+                                                                idx_b, scratch),
+                              8.0 * N + 8.0 * n_in + 12.0 * n_out),
+        "permute_wtb_to_twb": (lambda: tbe.tbe_permute_wtb_to_twb(W, T, B, len_b, idx_b, N, len_p, off_p, idx_p,
+                                                                  scratch),
+                               8.0 * N + 16.0 * n_out),
+        "lengths_to_offsets": (lambda: tbe.tbe_lengths_to_offsets(len_p, n_out, off_l, scratch), 12.0 * n_out),
+    }
+    res = {}
+    for name, (fn, nbytes) in calls.items():
+        for _ in range(args.warmup):
+            assert fn() == tbe.TBE_OK
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            assert fn() == tbe.TBE_OK
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        res[name] = {"ms": round(ms, 5), "algorithmic_bytes": nbytes,
+                     "algorithmic_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    assert torch.equal(off_l, off_p)
+    print(json.dumps({"metric": "input_side_kernels", "unit": "ms", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "dtype": "int32", "data": "synthetic",
+                      "config": {"workload": spec.name + "_inputs", "tables": T, "batch": B, "shards": W,
+                                 "lookups": N, "bags_in": n_in, "bags_out": n_out},
+                      "kernels": res}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -162,6 +216,9 @@ def main():
         spec = wl.config(args.config)
         if args.batch:
             spec.batch = args.batch
+    if args.inputs:
+        bench_inputs(args, spec, dev)
+        return
     t_setup = time.perf_counter()
     weights = wl.make_weights(spec, dev)
     batches = [wl.make_batch(spec, dev, it=i) for i in range(max(1, args.rotation))]

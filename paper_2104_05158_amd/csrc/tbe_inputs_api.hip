@@ -109,12 +109,17 @@ tbe_status_t tbe_permute_wtb_to_twb(int32_t W, int32_t T, int32_t B, const int32
     rc = enqueue_scan(d_lengths_in, n, s.offsets_in, s.block_sums, st);
     if (rc != TBE_OK)
         return rc;
-    const int blocks_per_row = (int)ceil_div(B, kThreads);
+    const int vec = B % 4 == 0 ? 4 : 1;
+    const int blocks_per_row = (int)ceil_div(B, kThreads * vec);
     const int64_t grid = (int64_t)W * T * blocks_per_row;
     if (grid > kMaxCount)
         return TBE_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(permute_lengths_kernel, dim3((unsigned)grid), dim3(kThreads), 0, st, d_lengths_in,
-                       d_lengths_out, W, T, B, blocks_per_row);
+    if (vec == 4)
+        hipLaunchKernelGGL(permute_lengths_kernel<4>, dim3((unsigned)grid), dim3(kThreads), 0, st, d_lengths_in,
+                           d_lengths_out, W, T, B, blocks_per_row);
+    else
+        hipLaunchKernelGGL(permute_lengths_kernel<1>, dim3((unsigned)grid), dim3(kThreads), 0, st, d_lengths_in,
+                           d_lengths_out, W, T, B, blocks_per_row);
     rc = enqueue_scan(d_lengths_out, n, d_offsets_out, s.block_sums, st);
     if (rc != TBE_OK)
         return rc;
@@ -149,21 +154,26 @@ tbe_status_t tbe_bucketize_rowwise(int32_t T, int32_t B, int32_t W, const int64_
     int wbits = 0;
     while ((1 << wbits) < W)
         ++wbits;
-    // enough wavefronts to fill the chip when the batch is small, whole 32-bag blocks when it is large
-    const int bpw = (int)std::min<int64_t>(kMaxBagsPerWave, std::max<int64_t>(1, n_in / 16384));
-    const unsigned grid = (unsigned)ceil_div(n_in, (int64_t)bpw * (kThreads / kWave));
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)ceil_div(n_out, kThreads * 4)), dim3(kThreads), 0, st,
-                       d_lengths_out, n_out, 0);
-    if (num_indices > 0)
-        hipLaunchKernelGGL(bucketize_kernel<false>, dim3(grid), dim3(kThreads), 0, st, d_rows, d_indices, d_offsets,
-                           d_lengths_out, (const int64_t*)nullptr, (int32_t*)nullptr, T, B, W, wbits, (int32_t)n_in,
-                           bpw);
+    // bags per workgroup: the LDS count table holds W * nbags <= 8192 entries; small batches get
+    // fewer bags per workgroup so that the grid still fills the chip
+    int nbags = std::min<int>(kBuckMaxBags, 8192 / W);
+    while (nbags > 8 && n_in / nbags < 2048)
+        nbags >>= 1;
+    const unsigned grid = (unsigned)ceil_div(n_in, nbags);
+    hipLaunchKernelGGL(bucketize_count_kernel, dim3(grid), dim3(kThreads), 0, st, d_rows, d_indices, d_offsets,
+                       d_lengths_out, T, B, W, (int32_t)n_in, nbags);
     rc = enqueue_scan(d_lengths_out, n_out, d_offsets_out, s.block_sums, st);
     if (rc != TBE_OK)
         return rc;
-    if (num_indices > 0)
-        hipLaunchKernelGGL(bucketize_kernel<true>, dim3(grid), dim3(kThreads), 0, st, d_rows, d_indices, d_offsets,
-                           d_lengths_out, d_offsets_out, d_indices_out, T, B, W, wbits, (int32_t)n_in, bpw);
+    if (num_indices > 0) {
+        if (W <= 32)
+            hipLaunchKernelGGL(bucketize_place_kernel<32>, dim3(grid), dim3(kThreads), 0, st, d_rows, d_indices,
+                               d_offsets, d_offsets_out, d_indices_out, T, B, W, wbits, (int32_t)n_in, nbags);
+        else
+            hipLaunchKernelGGL(bucketize_place_kernel<kMaxShards>, dim3(grid), dim3(kThreads), 0, st, d_rows,
+                               d_indices, d_offsets, d_offsets_out, d_indices_out, T, B, W, wbits, (int32_t)n_in,
+                               nbags);
+    }
     return launch_status();
 }
 
