@@ -24,7 +24,7 @@ namespace {
 
 enum Slot {
     SLOT_FORWARD = 0,
-    SLOT_BUILD_KEYS,
+    SLOT_SORT_PLAN,
     SLOT_RADIX_HIST,
     SLOT_RADIX_SCAN,
     SLOT_RADIX_SCATTER,
@@ -33,7 +33,7 @@ enum Slot {
     SLOT_LONG_FIXUP,
     SLOT_COUNT
 };
-const char* const kSlotNames[SLOT_COUNT] = {"forward",       "build_keys", "radix_hist",    "radix_scan",
+const char* const kSlotNames[SLOT_COUNT] = {"forward",       "sort_plan",  "radix_hist",    "radix_scan",
                                             "radix_scatter", "runlength",  "reduce_update", "long_fixup"};
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -72,6 +72,8 @@ struct tbe_s {
 
     // workspace layout (byte offsets)
     size_t off_meta = 0, off_rowbase = 0, off_counters = 0, off_keys[2] = {0, 0}, off_vals[2] = {0, 0};
+    size_t off_tile_base = 0, off_tstart = 0, off_tile_table = 0;
+    int64_t max_tiles = 1;
     size_t off_hist = 0, off_scan_tmp = 0, off_rl_counts = 0, off_chunk_first = 0, off_partials = 0;
     size_t off_long_list = 0, off_zero = 0, workspace_bytes = 0;
     size_t weight_bytes = 0, state_bytes = 0;
@@ -163,8 +165,12 @@ void plan_workspace(tbe_s* h)
         h->off_keys[i] = take(4 * nelem);
         h->off_vals[i] = take(4 * nelem);
     }
-    const int64_t sort_tiles = std::max<int64_t>(1, ceil_div(nmax, kSortTile));
-    const int64_t hist_len = 256 * sort_tiles;
+    // tiles never cross a table border: at most one partly filled tile per table on top of nmax / tile
+    h->max_tiles = ceil_div(nmax, kSortTile) + h->T;
+    h->off_tile_base = take(4 * (size_t)(h->T + 1));
+    h->off_tstart = take(4 * (size_t)(h->T + 1));
+    h->off_tile_table = take(4 * (size_t)h->max_tiles);
+    const int64_t hist_len = 256 * h->max_tiles;
     h->off_hist = take(4 * (size_t)hist_len);
     const int64_t rl_tiles = std::max<int64_t>(1, ceil_div(nmax, kRlTile));
     const int64_t scan_blocks = std::max(ceil_div(hist_len, kScanTile), ceil_div(rl_tiles, kScanTile));
@@ -303,8 +309,12 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
     h->dmax = dmax;
     h->fwd_epl = (h->dtype == TBE_DTYPE_FP16 && all8) ? 8 : 4;
     h->fwd_kmax = (int)ceil_div(dmax, h->fwd_epl * kWave);
+    // the sort is segmented by table, so only the bits of the tallest table's row index are sorted
+    int64_t max_rows = 1;
+    for (int t = 0; t < cfg->num_tables; ++t)
+        max_rows = std::max(max_rows, cfg->rows[t]);
     h->key_bits = 1;
-    while (h->key_bits < 32 && ((int64_t)1 << h->key_bits) < total_rows)
+    while (h->key_bits < 32 && ((int64_t)1 << h->key_bits) < max_rows)
         ++h->key_bits;
 
     h->woff.resize(h->T + 1);
@@ -433,44 +443,66 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
         h->final_buf = 0;
         return TBE_OK;
     }
-    const int num_bags = h->T * batch;
     const uint32_t* row_base = h->ws<uint32_t>(h->off_rowbase);
     uint32_t* keys[2] = {h->ws<uint32_t>(h->off_keys[0]), h->ws<uint32_t>(h->off_keys[1])};
     int32_t* vals[2] = {h->ws<int32_t>(h->off_vals[0]), h->ws<int32_t>(h->off_vals[1])};
 
-    {   // a2: (table,row) keys and bag payloads
-        ScopedTimer tm(h, SLOT_BUILD_KEYS, st);
-        hipLaunchKernelGGL(build_keys_kernel, dim3((unsigned)ceil_div(num_bags, kKeyBags)), dim3(256), 0, st,
-                           row_base, d_indices, d_offsets, keys[0], vals[0], batch, num_bags, counters);
-        TBE_LAUNCH_CHECK(h, "build_keys_kernel");
+    SortPlan pl;
+    pl.tile_base = h->ws<int32_t>(h->off_tile_base);
+    pl.tstart = h->ws<int32_t>(h->off_tstart);
+    pl.tile_table = h->ws<int32_t>(h->off_tile_table);
+    // upper bound of the number of tiles for THIS call (the exact number is only known on the device)
+    const int max_tiles = (int)std::min<int64_t>(h->max_tiles, ceil_div(n, kSortTile) + h->T);
+    {   // a2: table borders -> tile plan (keys are the caller's indices; payloads are made in the first pass)
+        ScopedTimer tm(h, SLOT_SORT_PLAN, st);
+        hipLaunchKernelGGL(sort_plan_tables_kernel, dim3(1), dim3(256), 0, st, d_offsets, batch, h->T,
+                           h->ws<int32_t>(h->off_tile_base), h->ws<int32_t>(h->off_tstart), counters);
+        hipLaunchKernelGGL(sort_plan_tiles_kernel, dim3((unsigned)ceil_div(max_tiles, 256)), dim3(256), 0, st,
+                           pl.tile_base, h->T, h->ws<int32_t>(h->off_tile_table), max_tiles);
+        TBE_LAUNCH_CHECK(h, "sort_plan kernels");
     }
 
-    // a3: stable LSD radix sort over only the significant key bits
+    // a3: stable LSD radix sort, segmented by table, over only the significant bits of the row index
     const int passes = (int)ceil_div(h->key_bits, 8);
-    const int num_tiles = (int)ceil_div(n, kSortTile);
     uint32_t* hist = h->ws<uint32_t>(h->off_hist);
-    int cur = 0, shift = 0;
+    const uint32_t* in_keys = reinterpret_cast<const uint32_t*>(d_indices);
+    const int32_t* in_vals = nullptr;
+    int cur = -1, shift = 0;  // cur: pair that holds the current order (-1 = the caller's arrays)
     for (int p = 0; p < passes; ++p) {
         const int bits = h->key_bits / passes + (p < h->key_bits % passes ? 1 : 0);
+        const int out = cur < 0 ? 0 : cur ^ 1;
         {
             ScopedTimer tm(h, SLOT_RADIX_HIST, st);
-            hipLaunchKernelGGL(radix_hist_kernel, dim3(num_tiles), dim3(kSortThreads), 0, st, keys[cur], hist,
-                               n, num_tiles, shift, bits);
+            hipLaunchKernelGGL(radix_hist_kernel, dim3(max_tiles), dim3(kSortThreads), 0, st, pl, in_keys, hist,
+                               shift, bits);
             TBE_LAUNCH_CHECK(h, "radix_hist_kernel");
         }
         {
             ScopedTimer tm(h, SLOT_RADIX_SCAN, st);
-            rc = device_scan(h, hist, (int64_t)num_tiles << bits, nullptr, st);
+            rc = device_scan(h, hist, (int64_t)max_tiles << bits, nullptr, st);
             if (rc != TBE_OK)
                 return rc;
         }
         {
             ScopedTimer tm(h, SLOT_RADIX_SCATTER, st);
-            hipLaunchKernelGGL(radix_scatter_kernel, dim3(num_tiles), dim3(kSortThreads), 0, st, keys[cur],
-                               vals[cur], keys[cur ^ 1], vals[cur ^ 1], hist, n, num_tiles, shift, bits);
+            const bool first = p == 0, last = p == passes - 1;
+#define SCATTER(F, L)                                                                                          \
+    hipLaunchKernelGGL((radix_scatter_kernel<F, L>), dim3(max_tiles), dim3(kSortThreads), 0, st, pl, in_keys, \
+                       in_vals, keys[out], vals[out], hist, d_offsets, row_base, batch, shift, bits)
+            if (first && last)
+                SCATTER(true, true);
+            else if (first)
+                SCATTER(true, false);
+            else if (last)
+                SCATTER(false, true);
+            else
+                SCATTER(false, false);
+#undef SCATTER
             TBE_LAUNCH_CHECK(h, "radix_scatter_kernel");
         }
-        cur ^= 1;
+        cur = out;
+        in_keys = keys[cur];
+        in_vals = vals[cur];
         shift += bits;
     }
     h->final_buf = cur;

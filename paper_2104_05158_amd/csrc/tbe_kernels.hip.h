@@ -22,7 +22,6 @@ constexpr int kWave = 64;
 constexpr int kFwdThreads = 256;          // 4 wavefronts per workgroup, each with its own block of bags
 constexpr int kFwdUnroll = 4;             // row loads in flight per lane group (8 costs occupancy and is slower)
 constexpr int kFwdMaxBagsPerWave = 8;     // measured best on configs 2-4 (4..32 tried)
-constexpr int kKeyBags = 256;             // bags per workgroup in the key build
 constexpr int kSortThreads = 512;         // 8 wavefronts
 constexpr int kSortKeysPerThread = 16;
 constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys staged in LDS
@@ -243,50 +242,142 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
     }
 }
 
-// ---------------------------------------------------------------- key build (Section 5.1, "sorting by rows")
-//
-// key[p] = rbase_t + indices[p] (the row's linear id over all tables), val[p] = b, for every lookup
-// position p.  A workgroup takes kKeyBags consecutive bags, keeps their offsets in LDS and walks the
-// positions they cover with coalesced loads/stores; the bag of a position is found by bisection in LDS.
-__global__ __launch_bounds__(256) void build_keys_kernel(
-    const uint32_t* __restrict__ row_base, const int32_t* __restrict__ indices,
-    const int64_t* __restrict__ offsets, uint32_t* __restrict__ keys, int32_t* __restrict__ vals,
-    int32_t B, int32_t num_bags, Counters* __restrict__ counters)
+// ---------------------------------------------------------------- workgroup scan helper (256 threads)
+
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* s_wave /*[4]*/,
+                                                             uint32_t& block_total)
 {
-    __shared__ int32_t soff[kKeyBags + 1];
-    const int j0 = blockIdx.x * kKeyBags;
-    const int nb = min(kKeyBags, num_bags - j0);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o)
+            incl += up;
+    }
+    if (lane == kWave - 1)
+        s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t woff = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t c = s_wave[w];
+        if (w < wave)
+            woff += c;
+        tot += c;
+    }
+    block_total = tot;
+    __syncthreads();
+    return woff + incl - v;
+}
+
+// ---------------------------------------------------------------- sort by (table, row)  (Section 5.1, "sorting by rows")
+//
+// The input is table-major, so the lookups of table t already occupy one contiguous range of
+// positions: sorting by (table, row) is a SEGMENTED sort in which every table is sorted by its own
+// row index.  That needs only ceil(log2 max_t H_t) key bits instead of ceil(log2 sum_t H_t), the first
+// pass can read the caller's indices directly as keys (the payload b, the bag's position inside its
+// table's batch, is derived from the offsets on the fly), and the last pass adds the table's row base
+// so that the result is sorted by the linear row id.
+//
+// Tiles of kSortTile positions never cross a table border.  A small plan (two launches) turns the
+// table borders offsets[t*B] into: the first tile of every table, the first position of every
+// table, and the table of every tile.  The per-tile digit histograms are laid out table by table,
+// digit-major inside a table: hist[tile_base[t]*nd + d*ntiles_t + local_tile].  One exclusive scan
+// over the whole array then yields global output positions, because every table's counts add up to
+// exactly its number of lookups.
+//
+// Per pass: (1) per-tile digit histogram, (2) the scan, (3) scatter: every wavefront ranks its
+// 16 x 64 keys with ballot-based digit matching into per-wave LDS counters, the tile is reordered by
+// digit inside LDS and then written out in runs that are contiguous in global memory.  Order inside
+// a tile is (wavefront, round, lane) = ascending position, so equal digits keep their input order
+// and the whole sort is stable.
+
+struct SortPlan {
+    const int32_t* tile_base;    // [T+1] first tile of table t; [T] = number of tiles
+    const int32_t* tstart;       // [T+1] first position of table t; [T] = n
+    const int32_t* tile_table;   // [max_tiles] table of tile g, -1 past the last tile
+};
+
+// one workgroup: table borders -> tile_base / tstart; also clears the per-call counters
+__global__ __launch_bounds__(256) void sort_plan_tables_kernel(const int64_t* __restrict__ offsets, int32_t B,
+                                                               int32_t T, int32_t* __restrict__ tile_base,
+                                                               int32_t* __restrict__ tstart,
+                                                               Counters* __restrict__ counters)
+{
+    __shared__ uint32_t s_wave[4];
+    if (threadIdx.x == 0) {
         counters->num_unique = 0;
         counters->long_count = 0;
     }
-    for (int i = threadIdx.x; i <= nb; i += 256)
-        soff[i] = (int32_t)offsets[j0 + i];
-    __syncthreads();
-    const int lo = soff[0], hi = soff[nb];
-    for (int p = lo + threadIdx.x; p < hi; p += 256) {
-        int a = 0, c = nb;  // soff[a] <= p < soff[c]
+    uint32_t carry = 0;
+    for (int base = 0; base < T; base += 256) {
+        const int t = base + threadIdx.x;
+        int32_t lo = 0, cnt = 0;
+        if (t < T) {
+            lo = (int32_t)offsets[(int64_t)t * B];
+            cnt = (int32_t)offsets[(int64_t)(t + 1) * B] - lo;
+        }
+        const uint32_t tiles = (uint32_t)((cnt + kSortTile - 1) / kSortTile);
+        uint32_t tot;
+        const uint32_t ex = block_exclusive_scan_256(tiles, s_wave, tot);
+        if (t < T) {
+            tile_base[t] = (int32_t)(carry + ex);
+            tstart[t] = lo;
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        tile_base[T] = (int32_t)carry;
+        tstart[T] = (int32_t)offsets[(int64_t)T * B];
+    }
+}
+
+__global__ __launch_bounds__(256) void sort_plan_tiles_kernel(const int32_t* __restrict__ tile_base, int32_t T,
+                                                              int32_t* __restrict__ tile_table, int32_t max_tiles)
+{
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= max_tiles)
+        return;
+    int t = -1;
+    if (g < tile_base[T]) {
+        int a = 0, c = T;  // last a in [0, T) with tile_base[a] <= g
         while (c - a > 1) {
             const int mid = (a + c) >> 1;
-            if (soff[mid] <= p)
+            if (tile_base[mid] <= g)
                 a = mid;
             else
                 c = mid;
         }
-        const int j = j0 + a;
-        const int t = j / B;
-        keys[p] = row_base[t] + (uint32_t)indices[p];
-        vals[p] = j - t * B;
+        t = a;
     }
+    tile_table[g] = t;
 }
 
-// ---------------------------------------------------------------- LSD radix sort (stable), LDS-staged
-//
-// Per pass: (1) per-tile digit histogram, (2) exclusive scan of the digit-major histogram table,
-// (3) scatter: every wavefront ranks its 16 x 64 keys with ballot-based digit matching into per-wave
-// LDS counters, the tile is reordered by digit inside LDS and then written out in runs that are
-// contiguous in global memory.  Order inside a tile is (wavefront, round, lane) = ascending position,
-// so equal digits keep their input order and the whole sort is stable.
+struct TileGeom {
+    int t;          // table
+    int first;      // first position of the tile
+    int cnt;        // positions in the tile (1..kSortTile)
+    int64_t hbase;  // index of this tile's digit-0 histogram entry
+    int hstride;    // distance between consecutive digits (tiles of the table)
+};
+
+__device__ __forceinline__ bool tile_geom(const SortPlan& pl, int g, int nd, TileGeom& tg)
+{
+    const int t = pl.tile_table[g];
+    if (t < 0)
+        return false;
+    const int tb = pl.tile_base[t];
+    const int lo = pl.tstart[t];
+    const int l = g - tb;
+    tg.t = t;
+    tg.first = lo + l * kSortTile;
+    tg.cnt = min(kSortTile, pl.tstart[t + 1] - tg.first);
+    tg.hstride = pl.tile_base[t + 1] - tb;
+    tg.hbase = (int64_t)tb * nd + l;
+    return true;
+}
 
 __device__ __forceinline__ uint64_t match_digit(uint32_t dg, bool valid, int bits)
 {
@@ -300,29 +391,32 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t dg, bool valid, int bit
 }
 
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
-    const uint32_t* __restrict__ keys, uint32_t* __restrict__ hist, int32_t n, int32_t num_tiles,
-    int shift, int bits)
+    SortPlan pl, const uint32_t* __restrict__ keys, uint32_t* __restrict__ hist, int shift, int bits)
 {
     __shared__ uint32_t s_hist[kSortThreads / kWave][256];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int nd = 1 << bits;
     const uint32_t mask = nd - 1;
+    TileGeom tg;
+    if (!tile_geom(pl, blockIdx.x, nd, tg))
+        return;
     for (int i = threadIdx.x; i < (kSortThreads / kWave) * 256; i += kSortThreads)
         (&s_hist[0][0])[i] = 0;
     __syncthreads();
     volatile uint32_t* wh = s_hist[wave];
-    const int base = blockIdx.x * kSortTile + wave * (kSortTile / (kSortThreads / kWave));
+    const int base = tg.first + wave * (kSortTile / (kSortThreads / kWave));
+    const int end = tg.first + tg.cnt;
     const uint64_t lt = (1ull << lane) - 1ull;
-    // all 16 key loads are issued before the first one is used (positions past n are clamped)
+    // all 16 key loads are issued before the first one is used (positions past the tile are clamped)
     uint32_t key[kSortKeysPerThread];
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r)
-        key[r] = keys[min(base + r * kWave + lane, n - 1)];
+        key[r] = keys[min(base + r * kWave + lane, end - 1)];
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
         const int q = base + r * kWave + lane;
-        const bool valid = q < n;
+        const bool valid = q < end;
         const uint32_t dg = (key[r] >> shift) & mask;
         const uint64_t peers = match_digit(dg, valid, bits);
         if (valid && (peers & lt) == 0)
@@ -334,14 +428,18 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
 #pragma unroll
         for (int w = 0; w < kSortThreads / kWave; ++w)
             s += s_hist[w][d];
-        hist[(int64_t)d * num_tiles + blockIdx.x] = s;
+        hist[tg.hbase + (int64_t)d * tg.hstride] = s;
     }
 }
 
+// FIRST: keys_in is the caller's index array and the payload is computed from the offsets;
+// LAST: the table's row base is added to the keys that are written out.
+template <bool FIRST, bool LAST>
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
-    const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
+    SortPlan pl, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
     uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
-    const uint32_t* __restrict__ hist_scanned, int32_t n, int32_t num_tiles, int shift, int bits)
+    const uint32_t* __restrict__ hist_scanned, const int64_t* __restrict__ offsets,
+    const uint32_t* __restrict__ row_base, int32_t B, int shift, int bits)
 {
     constexpr int kWaves = kSortThreads / kWave;
     __shared__ uint32_t s_keys[kSortTile];
@@ -349,35 +447,94 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     __shared__ uint32_t s_whist[kWaves][256];
     __shared__ uint32_t s_dstart[256];
     __shared__ uint32_t s_goff[256];
+    __shared__ int32_t s_bag[2];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int nd = 1 << bits;
     const uint32_t mask = nd - 1;
-    const int tile = blockIdx.x;
-    const int tile_base = tile * kSortTile;
-    const int tile_cnt = min(kSortTile, n - tile_base);
+    TileGeom tg;
+    if (!tile_geom(pl, blockIdx.x, nd, tg))
+        return;
+    const int tile_cnt = tg.cnt;
+    const int end = tg.first + tile_cnt;
 
     for (int i = threadIdx.x; i < kWaves * 256; i += kSortThreads)
         (&s_whist[0][0])[i] = 0;
+    if (FIRST && threadIdx.x < 2) {
+        // bag (inside table t) of the tile's first / last position: last j with offsets[j] <= q
+        const int64_t q = threadIdx.x == 0 ? tg.first : end - 1;
+        const int64_t j0 = (int64_t)tg.t * B;
+        int a = 0, c = B;
+        while (c - a > 1) {
+            const int mid = (a + c) >> 1;
+            if (offsets[j0 + mid] <= q)
+                a = mid;
+            else
+                c = mid;
+        }
+        s_bag[threadIdx.x] = a;
+    }
     __syncthreads();
 
     uint32_t key[kSortKeysPerThread];
     int32_t val[kSortKeysPerThread];
     uint32_t rank[kSortKeysPerThread];
-    const int base = tile_base + wave * (kSortTile / kWaves);
+    const int base = tg.first + wave * (kSortTile / kWaves);
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
-        const int q = base + r * kWave + lane;
-        key[r] = keys_in[min(q, n - 1)];
-        val[r] = vals_in[min(q, n - 1)];
+        const int q = min(base + r * kWave + lane, end - 1);
+        key[r] = keys_in[q];
+        if (!FIRST)
+            val[r] = vals_in[q];
+    }
+    if (FIRST) {
+        // payload = bag of the position: the borders of the bags the tile touches are staged in
+        // LDS (in the space the reordered payloads use later) and searched there
+        const int b_lo = s_bag[0], b_hi = s_bag[1];
+        const int nb = b_hi - b_lo + 1;
+        const int64_t j0 = (int64_t)tg.t * B + b_lo;
+        if (nb <= kSortTile) {
+            for (int i = threadIdx.x; i < nb; i += kSortThreads)
+                s_vals[i] = (int32_t)offsets[j0 + i];
+            __syncthreads();
+            int steps = 0;
+            while ((1 << steps) < nb)
+                ++steps;
+#pragma unroll
+            for (int r = 0; r < kSortKeysPerThread; ++r) {
+                const int q = min(base + r * kWave + lane, end - 1);
+                int a = 0, c = nb;  // last a with s_vals[a] <= q
+                for (int st = 0; st < steps; ++st) {
+                    const int mid = (a + c) >> 1;
+                    const bool up = s_vals[mid] <= q;
+                    a = up ? mid : a;
+                    c = up ? c : max(mid, a + 1);
+                }
+                val[r] = b_lo + a;
+            }
+        } else {
+#pragma unroll 1
+            for (int r = 0; r < kSortKeysPerThread; ++r) {
+                const int q = min(base + r * kWave + lane, end - 1);
+                int a = 0, c = nb;
+                while (c - a > 1) {
+                    const int mid = (a + c) >> 1;
+                    if (offsets[j0 + mid] <= q)
+                        a = mid;
+                    else
+                        c = mid;
+                }
+                val[r] = b_lo + a;
+            }
+        }
     }
     volatile uint32_t* wh = s_whist[wave];
     const uint64_t lt = (1ull << lane) - 1ull;
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
         const int q = base + r * kWave + lane;
-        const bool valid = q < n;
+        const bool valid = q < end;
         const uint32_t dg = (key[r] >> shift) & mask;
         const uint64_t peers = match_digit(dg, valid, bits);
         const uint32_t pre = valid ? wh[dg] : 0u;
@@ -423,7 +580,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             const int d = lane * 4 + i;
             if (d < nd) {
                 s_dstart[d] = ex;
-                s_goff[d] = hist_scanned[(int64_t)d * num_tiles + tile] - ex;
+                s_goff[d] = hist_scanned[tg.hbase + (int64_t)d * tg.hstride] - ex;
             }
             ex += c[i];
         }
@@ -433,7 +590,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
         const int q = base + r * kWave + lane;
-        if (q < n) {
+        if (q < end) {
             const uint32_t dg = (key[r] >> shift) & mask;
             const uint32_t pos = s_dstart[dg] + s_whist[wave][dg] + rank[r];
             s_keys[pos] = key[r];
@@ -441,47 +598,20 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
         }
     }
     __syncthreads();
+    const uint32_t add = LAST ? row_base[tg.t] : 0u;
 #pragma unroll
     for (int i = 0; i < kSortKeysPerThread; ++i) {
         const int p = threadIdx.x + i * kSortThreads;
         if (p < tile_cnt) {
             const uint32_t k = s_keys[p];
             const uint32_t g = s_goff[(k >> shift) & mask] + (uint32_t)p;
-            keys_out[g] = k;
+            keys_out[g] = k + add;
             vals_out[g] = s_vals[p];
         }
     }
 }
 
 // ---------------------------------------------------------------- device-wide exclusive scan (uint32)
-
-__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* s_wave /*[4]*/,
-                                                             uint32_t& block_total)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
-    uint32_t incl = v;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o);
-        if (lane >= o)
-            incl += up;
-    }
-    if (lane == kWave - 1)
-        s_wave[wave] = incl;
-    __syncthreads();
-    uint32_t woff = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        const uint32_t c = s_wave[w];
-        if (w < wave)
-            woff += c;
-        tot += c;
-    }
-    block_total = tot;
-    __syncthreads();
-    return woff + incl - v;
-}
 
 __global__ __launch_bounds__(kScanThreads) void scan_reduce_kernel(
     const uint32_t* __restrict__ data, uint32_t* __restrict__ block_sums, int64_t n)
