@@ -8,8 +8,9 @@ the timed region; a rotation of pre-generated batches (different seeds) is used 
 re-reads the previous step's index stream.
 
 Prints ONE JSON line: lookups/s of fwd+bwd (whole job = this one GPU), plus
-  roofline      -- the dominant kernel's algorithmic bytes per launch / its mean launch duration,
-                   measured with HIP events recorded by the library on the launch stream
+  roofline      -- the dominant kernel's algorithmic (compulsory: each distinct byte once) bytes per launch /
+                   its mean launch duration, measured with HIP events recorded by the library on the launch
+                   stream; the every-lookup-counted ("logical") rate is given beside it
   cpu_baseline  -- the CPU oracle, as it stands, timed on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -62,27 +63,39 @@ def per_table_counts(spec, batch):
     return np.diff(bounds.cpu().numpy())
 
 
-def kernel_bytes(spec, n_t, u_t, key_passes):
-    """Algorithmic bytes one launch of each kernel must move (logical: every lookup counted)."""
+LONG_RUN = 512    # runs longer than this are cut at 128-position chunk borders by the library (kLongRun)
+
+
+def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t):
+    """Bytes one launch of each kernel must move, two ways.
+    compulsory: every distinct byte once -- what an ideal cache would leave for HBM; the roofline numerator.
+    logical:    every lookup counted as a row read -- a throughput figure that caches can push past the HBM peak.
+    n_t / u_t: lookups / distinct rows per table; nlong_t / ulong_t: lookups in / number of runs longer than LONG_RUN."""
     sw = 4 if spec.dtype == 0 else 2
     D = spec.dims.astype(np.float64)
     B = float(spec.batch)
     N = float(n_t.sum())
     U = float(u_t.sum())
     bags = float(spec.T) * B
-    fwd = float((n_t * (D * sw + 4)).sum() + (B * (8 + 4 * D)).sum())
-    upd = float(N * 4 + (n_t * 4 * D).sum() + (u_t * (2 * D * sw + 8)).sum() + U * 8)
-    return {
-        "forward": fwd,
-        "build_keys": N * 4 + bags * 8 + N * 8,
+    io_fwd = N * 4 + bags * 8 + (B * 4 * D).sum()
+    rmw = (u_t * (2 * D * sw + 8)).sum()
+    slab = B * 4 * D
+    partial_rows = nlong_t / 128.0 + 2 * ulong_t    # one fp32 partial row per chunk a long run touches
+    comp = {
+        "forward": float((u_t * D * sw).sum() + io_fwd),
+        "sort_plan": 0.0,
         "radix_hist": N * 4,
         "radix_scatter": N * 16,
         "radix_scan": 0.0,
-        "runlength": N * 8 + U * 8,
-        "reduce_update": upd,
-        "long_fixup": 0.0,
-        "compulsory_forward": float((u_t * D * sw).sum() + N * 4 + (B * (8 + 4 * D)).sum()),
+        "runlength": N * 4 + U * 8,
+        "reduce_update": float(N * 4 + U * 8 + np.minimum(n_t * 4 * D, slab).sum() + rmw +
+                               (partial_rows * 4 * D).sum()),
+        "long_fixup": float((partial_rows * 4 * D + ulong_t * (2 * D * sw + 8)).sum()),
     }
+    logical = dict(comp)
+    logical["forward"] = float((n_t * D * sw).sum() + io_fwd)
+    logical["reduce_update"] = float(N * 4 + U * 8 + (n_t * 4 * D).sum() + rmw + (partial_rows * 4 * D).sum())
+    return comp, logical
 
 
 def cpu_baseline(spec, batch, weights, grad, target_lookups):
@@ -279,6 +292,8 @@ def main():
     # workload statistics of the last batch used (for the byte model)
     last = batches[(args.warmup + args.steps - 1) % len(batches)]
     n_t = per_table_counts(spec, last).astype(np.float64)
+    nlong_t = np.zeros(spec.T)
+    ulong_t = np.zeros(spec.T)
     if args.fwd_only:
         u_t = np.zeros(spec.T)
         num_unique = 0
@@ -289,24 +304,29 @@ def main():
         uk = art["unique_keys"].to(torch.int64) & 0xFFFFFFFF
         tab = torch.searchsorted(R, uk, right=True) - 1
         u_t = torch.bincount(tab, minlength=spec.T).cpu().numpy().astype(np.float64)
-    key_bits = max(1, int(np.ceil(np.log2(max(2, spec.total_rows)))))
-    passes = (key_bits + 7) // 8
-    kb = kernel_bytes(spec, n_t, u_t, passes)
+        lens = torch.diff(art["seg_offsets"].to(torch.int64))
+        is_long = lens > LONG_RUN
+        nlong_t = torch.bincount(tab[is_long], weights=lens[is_long].double(), minlength=spec.T).cpu().numpy()
+        ulong_t = torch.bincount(tab[is_long], minlength=spec.T).cpu().numpy().astype(np.float64)
+    comp, logical = kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t)
 
     kernels = {}
     for name, (launches, ms) in prof.items():
         if launches:
             per = ms / launches
-            per_step = ms / args.steps
+            gbps = lambda d: round(d.get(name, 0.0) / (per * 1e-3) / 1e9, 1) if per > 0 else None
             kernels[name] = {"launches_per_step": launches / args.steps, "ms_per_launch": round(per, 5),
-                             "ms_per_step": round(per_step, 5),
-                             "algorithmic_GBps": round(kb.get(name, 0.0) / (per * 1e-3) / 1e9, 1) if per > 0 else None}
+                             "ms_per_step": round(ms / args.steps, 5), "compulsory_GBps": gbps(comp),
+                             "logical_GBps": gbps(logical)}
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     dom_ms = kernels[dominant]["ms_per_launch"]
-    achieved = kb[dominant] / (dom_ms * 1e-3) / 1e9
+    achieved = comp[dominant] / (dom_ms * 1e-3) / 1e9
+    # achieved = compulsory algorithmic bytes of that kernel / its mean duration (HIP events on the launch stream)
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "algorithmic_bytes_per_launch": kb[dominant], "ms_per_launch": dom_ms}
+                "algorithmic_bytes_per_launch": comp[dominant], "ms_per_launch": dom_ms,
+                "logical_bytes_per_launch": logical[dominant],
+                "logical_GBps": round(logical[dominant] / (dom_ms * 1e-3) / 1e9, 1)}
     # measured L2<->fabric bytes per launch of that kernel (two rocprofv3 --pmc runs, summarised in profiles/)
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(traffic_file):
@@ -349,8 +369,7 @@ def main():
         "kernels": kernels,
         "fwd_ms": fwd_ms,
         "bwd_ms": round(bwd_ms, 5),
-        "logical_GBps_fwd": round(kb["forward"] / (fwd_ms * 1e-3) / 1e9, 1) if fwd_ms else None,
-        "compulsory_GBps_fwd": round(kb["compulsory_forward"] / (fwd_ms * 1e-3) / 1e9, 1) if fwd_ms and not args.fwd_only else None,
+        "step_compulsory_GBps": round(sum(comp.values()) / (ms_per_step * 1e-3) / 1e9, 1) if not args.fwd_only else None,
         "setup_s": round(setup_s, 2),
     }
     if not args.no_cpu_baseline:
