@@ -34,8 +34,9 @@
  *   d_offsets         int64[num_tables*batch + 1], non-decreasing, first 0, last num_indices
  *   weights           one flat array in the storage type; table t is the row-major block of
  *                     rows[t] x dims[t] elements starting at element weight_offsets[t]
- *   state             float32; the moment of row r of table t is element state_offsets[t] + r
- *   output / grad     float32 [batch, sum_t dims[t]] row-major; table t owns columns
+ *   state             float32; row-wise AdaGrad: the moment of row r of table t is element
+ *                     state_offsets[t] + r (other optimizers: see tbe_config_t)
+ *   output / grad     [batch, sum_t dims[t]] row-major, float32 unless configured otherwise; table t owns columns
  *                     [out_col_offsets[t], out_col_offsets[t] + dims[t])
  *   linear row id     key = state_offsets[t] + row  (uint32; the sort key of the backward pass)
  */
@@ -67,8 +68,11 @@ typedef enum {
     TBE_ERR_HIP = 6
 } tbe_status_t;
 
-enum { TBE_DTYPE_FP32 = 0, TBE_DTYPE_FP16 = 1 };
+enum { TBE_DTYPE_FP32 = 0, TBE_DTYPE_FP16 = 1, TBE_DTYPE_BF16 = 2 };
 enum { TBE_POOLING_SUM = 0 };
+/* Sparse optimizer fused into the backward pass.  Section 5.2 describes the row-wise AdaGrad;
+ * Section 5.1 names (element-wise) AdaGrad and Adam as further non-linear optimizers it serves. */
+enum { TBE_OPT_ROWWISE_ADAGRAD = 0, TBE_OPT_ADAGRAD = 1, TBE_OPT_ADAM = 2 };
 
 typedef struct {
     int32_t num_tables;     /* T >= 1 */
@@ -78,14 +82,24 @@ typedef struct {
     int32_t pooling;        /* TBE_POOLING_SUM is the only mode */
     int32_t max_batch;      /* largest `batch` any later call will pass; T*max_batch < 2^31 */
     int64_t max_indices;    /* largest `num_indices` any later call will pass; < 2^31 - 2^24 */
+    int32_t optimizer;      /* TBE_OPT_*: fixes the size of the state buffer and which backward entry points apply */
+    int32_t output_dtype;   /* type of d_out: TBE_DTYPE_FP32, or TBE_DTYPE_FP16 (fp32 sums rounded to nearest even) */
+    int32_t grad_dtype;     /* type of d_grad_out: TBE_DTYPE_FP32, TBE_DTYPE_FP16 or TBE_DTYPE_BF16; sums stay fp32 */
+    int32_t reserved;       /* 0 */
 } tbe_config_t;
+/* The 16-bit output / gradient types follow Section 8.4: the pooled embeddings leave the operator
+ * through an FP16 all-to-all and their gradients come back through a BF16 one, so that precision is
+ * all that is there to consume.  Optimizer state (float32, zero-filled by the caller before step 1):
+ *   TBE_OPT_ROWWISE_ADAGRAD  one moment per table row (linear row id)                 4 * sum_t rows[t]
+ *   TBE_OPT_ADAGRAD          one sum of squares per weight element (weight layout)     4 * sum_t rows[t]*dims[t]
+ *   TBE_OPT_ADAM             first moments of all elements, then all second moments    8 * sum_t rows[t]*dims[t] */
 
 /*
  * Creates a handle (host only; copies the config arrays).  Section 5.1: one handle stands for all
  * tables that are fused into one operator on this GPU.
  * Errors: INVALID_ARG (null, T < 1, rows/dims not positive, negative sizes),
  *         UNSUPPORTED (dim not a multiple of 4 or > 512, sum of rows >= 2^32 - 1, sizes too large,
- *         unknown dtype/pooling).
+ *         unknown dtype/pooling/optimizer, BF16 tables or BF16 output, reserved != 0).
  */
 TBE_API tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle);
 
@@ -95,7 +109,9 @@ TBE_API tbe_status_t tbe_destroy(tbe_handle_t h);
 /*
  * Sizes (bytes) of the three device buffers the caller must provide, and the layout tables
  * described above.  Any output pointer may be NULL.  weight_offsets / state_offsets are host
- * int64[T+1] in ELEMENTS, out_col_offsets is host int32[T+1].
+ * int64[T+1] in ELEMENTS, out_col_offsets is host int32[T+1].  state_offsets are the linear row
+ * ids of the tables' first rows (the index of the row-wise moments and the base of the sort keys);
+ * per-element optimizer states are indexed by weight_offsets.
  */
 TBE_API tbe_status_t tbe_query_sizes(tbe_handle_t h, size_t* weight_bytes, size_t* state_bytes,
                              size_t* workspace_bytes, int64_t* weight_offsets,
@@ -103,9 +119,9 @@ TBE_API tbe_status_t tbe_query_sizes(tbe_handle_t h, size_t* weight_bytes, size_
 
 /*
  * Lends the device buffers to the handle and uploads the table metadata into the head of the
- * workspace (synchronous copy).  d_weights: storage type, weight_bytes; d_state: float32 moments,
- * state_bytes, zero-filled by the caller before the first step (Section 5.2 keeps one moment per
- * row; its start value is not given, 0 is used); d_workspace: at least workspace_bytes,
+ * workspace (synchronous copy).  d_weights: storage type, weight_bytes; d_state: float32 optimizer
+ * state, state_bytes, zero-filled by the caller before the first step (Section 5.2 keeps one moment
+ * per row; its start value is not given, 0 is used); d_workspace: at least workspace_bytes,
  * 256-byte aligned.  Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, HIP.
  */
 TBE_API tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_workspace,
@@ -115,11 +131,11 @@ TBE_API tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, v
  * Forward (Section 2 "Embedding operators", fused over tables per Section 5.1):
  *   d_out[b, c_t + d] = sum_{p in bag (t,b)} W_t[d_indices[p], d]      accumulated in fp32
  * One kernel launch for all tables.  An empty bag pools to 0.  Indices are assumed valid
- * (see tbe_check_inputs).  d_out is float32 [batch, sumD], written completely.
+ * (see tbe_check_inputs).  d_out is [batch, sumD] in the configured output type, written completely.
  * Errors: NOT_BOUND, INVALID_ARG (null, batch < 0 or > max_batch, num_indices < 0 or > max_indices), HIP.
  */
 TBE_API tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
-                         int64_t num_indices, int32_t batch, float* d_out, void* stream);
+                         int64_t num_indices, int32_t batch, void* d_out, void* stream);
 
 /*
  * Backward fused with row-wise AdaGrad, in place (Sections 5.1 and 5.2).  With
@@ -132,28 +148,52 @@ TBE_API tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const
  * written.  Implementation: (table,row) keys are built, radix-sorted (stable) and run-length
  * segmented in the workspace, then every run is reduced on chip and its row updated once.
  * The integer artefacts stay in the workspace until the next backward call (tbe_backward_artifacts).
- * Errors: as tbe_forward.
+ * d_grad_out is [batch, sumD] in the configured gradient type.
+ * Errors: as tbe_forward; INVALID_ARG if the handle was created for another optimizer.
  */
 TBE_API tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
                                           const int64_t* d_offsets, int64_t num_indices,
-                                          int32_t batch, const float* d_grad_out, float lr,
+                                          int32_t batch, const void* d_grad_out, float lr,
                                           float eps, void* stream);
+
+/*
+ * The same fused backward with the other optimizers Section 5.1 names; G is aggregated exactly as
+ * above and every touched row gets one step, element by element (d over the row's columns):
+ *   AdaGrad   S[t,r,d] += G_d^2;   W_t[r,d] -= lr * G_d / (sqrt(S[t,r,d]) + eps)
+ *   Adam      m = beta1*m + (1-beta1)*G_d;   v = beta2*v + (1-beta2)*G_d^2;
+ *             W_t[r,d] -= lr * (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps)
+ * Adam is the lazy sparse form: rows that the batch does not look up keep weights and moments;
+ * `step` >= 1 is the caller's global iteration count (bias correction).  The paper gives no
+ * formulas for these; they are the textbook rules with the conventions of the row-wise form
+ * (updated state scales the step, eps outside the root, states start at 0).
+ * Errors: as above; Adam with step < 1 or beta outside [0,1) returns INVALID_ARG.
+ */
+TBE_API tbe_status_t tbe_backward_adagrad(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                                          int64_t num_indices, int32_t batch, const void* d_grad_out, float lr,
+                                          float eps, void* stream);
+TBE_API tbe_status_t tbe_backward_adam(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                                       int64_t num_indices, int32_t batch, const void* d_grad_out, float lr,
+                                       float beta1, float beta2, float eps, int64_t step, void* stream);
 
 /*
  * The same backward pass in two calls, for callers that overlap work (Section 4.2 pipelines
  * independent stages on separate streams).  tbe_backward_sort enqueues the part that needs only the
  * batch's (indices, offsets): key build, radix sort, run-length segmentation (Section 5.1 "gradient
  * sorting by rows"); it may run on another stream, concurrently with tbe_forward or with dense
- * layers.  tbe_backward_update_rowwise_adagrad enqueues the aggregation + optimizer step
+ * layers.  tbe_backward_update_<optimizer> enqueues the aggregation + optimizer step
  * (Sections 5.1, 5.2) for the batch sorted last; the caller must order it after that sort (same
  * stream, or an event) and must not start the next sort of this handle before it has finished:
- * both use the handle's workspace.  tbe_backward_rowwise_adagrad is exactly these two in a row.
+ * both use the handle's workspace.  tbe_backward_<optimizer> is exactly these two in a row.
  * Errors: as tbe_forward; update without a preceding sort returns INVALID_ARG.
  */
 TBE_API tbe_status_t tbe_backward_sort(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
                                        int64_t num_indices, int32_t batch, void* stream);
-TBE_API tbe_status_t tbe_backward_update_rowwise_adagrad(tbe_handle_t h, const float* d_grad_out, float lr,
+TBE_API tbe_status_t tbe_backward_update_rowwise_adagrad(tbe_handle_t h, const void* d_grad_out, float lr,
                                                          float eps, void* stream);
+TBE_API tbe_status_t tbe_backward_update_adagrad(tbe_handle_t h, const void* d_grad_out, float lr, float eps,
+                                                 void* stream);
+TBE_API tbe_status_t tbe_backward_update_adam(tbe_handle_t h, const void* d_grad_out, float lr, float beta1,
+                                              float beta2, float eps, int64_t step, void* stream);
 
 /*
  * Device pointers (into the workspace) of the last backward call's integer artefacts

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -58,6 +59,10 @@ struct tbe_s {
     std::vector<int64_t> rows;
     std::vector<int32_t> dims;
     int dtype = 0;
+    int optimizer = 0;
+    int out_dtype = 0;
+    int grad_dtype = 0;
+    int64_t weight_elems = 0;
     int max_batch = 0;
     int64_t max_indices = 0;
     int64_t sumD = 0;
@@ -211,9 +216,9 @@ tbe_status_t check_call(tbe_s* h, const void* d_indices, const void* d_offsets, 
     return TBE_OK;
 }
 
-template <typename WT>
+template <typename WT, typename OT>
 tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, int32_t n_total, int32_t batch,
-                            float* out, hipStream_t st)
+                            OT* out, hipStream_t st)
 {
     const int num_bags = h->T * batch;
     // bags per wavefront: enough to amortise the per-block prologue, few enough to keep >= ~16k
@@ -226,7 +231,7 @@ tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, in
     const int sumD = (int)h->sumD;
     const void* zero = h->ws<void>(h->off_zero);
 #define FWD(EPL, KMAX)                                                                              \
-    hipLaunchKernelGGL((forward_kernel<WT, EPL, KMAX>), grid, block, 0, st, meta, w, idx, off, out, \
+    hipLaunchKernelGGL((forward_kernel<WT, EPL, KMAX, OT>), grid, block, 0, st, meta, w, idx, off, out, \
                        zero, batch, num_bags, sumD, n_total, bpw)
     if constexpr (sizeof(WT) == 4) {
         if (h->fwd_kmax == 1)
@@ -275,7 +280,12 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
         if (cfg->rows[t] <= 0 || cfg->dims[t] <= 0)
             return TBE_ERR_INVALID_ARG;
     if ((cfg->weight_dtype != TBE_DTYPE_FP32 && cfg->weight_dtype != TBE_DTYPE_FP16) ||
-        cfg->pooling != TBE_POOLING_SUM)
+        cfg->pooling != TBE_POOLING_SUM || cfg->reserved != 0 ||
+        (cfg->optimizer != TBE_OPT_ROWWISE_ADAGRAD && cfg->optimizer != TBE_OPT_ADAGRAD &&
+         cfg->optimizer != TBE_OPT_ADAM) ||
+        (cfg->output_dtype != TBE_DTYPE_FP32 && cfg->output_dtype != TBE_DTYPE_FP16) ||
+        (cfg->grad_dtype != TBE_DTYPE_FP32 && cfg->grad_dtype != TBE_DTYPE_FP16 &&
+         cfg->grad_dtype != TBE_DTYPE_BF16))
         return TBE_ERR_UNSUPPORTED;
     if (cfg->max_indices >= ((int64_t)1 << 31) - ((int64_t)1 << 24) ||
         (int64_t)cfg->num_tables * cfg->max_batch >= ((int64_t)1 << 31) - 1024)
@@ -303,6 +313,9 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
     h->rows.assign(cfg->rows, cfg->rows + h->T);
     h->dims.assign(cfg->dims, cfg->dims + h->T);
     h->dtype = cfg->weight_dtype;
+    h->optimizer = cfg->optimizer;
+    h->out_dtype = cfg->output_dtype;
+    h->grad_dtype = cfg->grad_dtype;
     h->max_batch = cfg->max_batch;
     h->max_indices = cfg->max_indices;
     h->sumD = sumD;
@@ -342,8 +355,11 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
     h->woff[h->T] = w;
     h->soff[h->T] = s;
     h->coloff[h->T] = c;
+    h->weight_elems = w;
     h->weight_bytes = (size_t)w * (h->dtype == TBE_DTYPE_FP32 ? 4 : 2);
-    h->state_bytes = (size_t)s * 4;
+    h->state_bytes = h->optimizer == TBE_OPT_ROWWISE_ADAGRAD ? (size_t)s * 4
+                     : h->optimizer == TBE_OPT_ADAGRAD       ? (size_t)w * 4
+                                                             : (size_t)w * 8;
     plan_workspace(h);
     *out_handle = h;
     return TBE_OK;
@@ -386,7 +402,7 @@ tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_w
     if (!h || !d_weights || !d_state || !d_workspace)
         return TBE_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(d_workspace) & 255) || (reinterpret_cast<uintptr_t>(d_weights) & 15) ||
-        (reinterpret_cast<uintptr_t>(d_state) & 3))
+        (reinterpret_cast<uintptr_t>(d_state) & (h->optimizer == TBE_OPT_ROWWISE_ADAGRAD ? 3 : 15)))
         return TBE_ERR_INVALID_ARG;
     if (workspace_bytes < h->workspace_bytes)
         return TBE_ERR_WORKSPACE_TOO_SMALL;
@@ -413,7 +429,7 @@ tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_w
 }
 
 tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
-                         int64_t num_indices, int32_t batch, float* d_out, void* stream)
+                         int64_t num_indices, int32_t batch, void* d_out, void* stream)
 {
     tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
     if (rc != TBE_OK)
@@ -424,9 +440,17 @@ tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t
         return TBE_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     ScopedTimer tm(h, SLOT_FORWARD, st);
+    const int32_t n = (int32_t)num_indices;
+    if (h->out_dtype == TBE_DTYPE_FP32) {
+        float* out = static_cast<float*>(d_out);
+        if (h->dtype == TBE_DTYPE_FP32)
+            return launch_forward<float, float>(h, d_indices, d_offsets, n, batch, out, st);
+        return launch_forward<__half, float>(h, d_indices, d_offsets, n, batch, out, st);
+    }
+    __half* out = static_cast<__half*>(d_out);
     if (h->dtype == TBE_DTYPE_FP32)
-        return launch_forward<float>(h, d_indices, d_offsets, (int32_t)num_indices, batch, d_out, st);
-    return launch_forward<__half>(h, d_indices, d_offsets, (int32_t)num_indices, batch, d_out, st);
+        return launch_forward<float, __half>(h, d_indices, d_offsets, n, batch, out, st);
+    return launch_forward<__half, __half>(h, d_indices, d_offsets, n, batch, out, st);
 }
 
 // a2..a4: needs only the batch's (indices, offsets)
@@ -531,7 +555,50 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
 }
 
 // a5 + a6 on the artefacts left by enqueue_sort
-static tbe_status_t enqueue_update(tbe_s* h, const float* d_grad_out, float lr, float eps, hipStream_t st)
+extern "C++" {
+template <typename WT, typename GT, int OPT>
+static void launch_update(const BwdArgs& a, dim3 grid, dim3 grid_fix, hipStream_t st, tbe_s* h)
+{
+    {
+        ScopedTimer tm(h, SLOT_REDUCE_UPDATE, st);
+        hipLaunchKernelGGL((reduce_update_kernel<WT, GT, OPT>), grid, dim3(kBwdThreads), 0, st, a);
+    }
+    {
+        ScopedTimer tm(h, SLOT_LONG_FIXUP, st);
+        hipLaunchKernelGGL((long_run_fixup_kernel<WT, OPT>), grid_fix, dim3(kBwdThreads), 0, st, a);
+    }
+}
+
+template <typename WT, typename GT>
+static void launch_update_opt(const BwdArgs& a, dim3 grid, dim3 grid_fix, hipStream_t st, tbe_s* h)
+{
+    if (h->optimizer == TBE_OPT_ROWWISE_ADAGRAD)
+        launch_update<WT, GT, kOptRowwiseAdagrad>(a, grid, grid_fix, st, h);
+    else if (h->optimizer == TBE_OPT_ADAGRAD)
+        launch_update<WT, GT, kOptAdagrad>(a, grid, grid_fix, st, h);
+    else
+        launch_update<WT, GT, kOptAdam>(a, grid, grid_fix, st, h);
+}
+
+template <typename WT>
+static void launch_update_grad(const BwdArgs& a, dim3 grid, dim3 grid_fix, hipStream_t st, tbe_s* h)
+{
+    if (h->grad_dtype == TBE_DTYPE_FP32)
+        launch_update_opt<WT, float>(a, grid, grid_fix, st, h);
+    else if (h->grad_dtype == TBE_DTYPE_FP16)
+        launch_update_opt<WT, __half>(a, grid, grid_fix, st, h);
+    else
+        launch_update_opt<WT, __hip_bfloat16>(a, grid, grid_fix, st, h);
+}
+}  // extern "C++"
+
+struct OptCall {   // what the caller passed for this step
+    int optimizer;
+    float lr, eps, beta1, beta2;
+    int64_t step;
+};
+
+static tbe_status_t enqueue_update(tbe_s* h, const void* d_grad_out, const OptCall& oc, hipStream_t st)
 {
     const int32_t n = h->sorted_n;
     if (h->sorted_batch == 0 || n == 0)
@@ -559,7 +626,6 @@ static tbe_status_t enqueue_update(tbe_s* h, const float* d_grad_out, float lr, 
     a.counters = counters;
     a.grad_out = d_grad_out;
     a.weights = h->d_weights;
-    a.moments = h->d_state;
     a.partials = h->ws<float>(h->off_partials);
     a.long_list = h->ws<uint32_t>(h->off_long_list);
     a.zero_row = h->ws<float>(h->off_zero);
@@ -568,28 +634,28 @@ static tbe_status_t enqueue_update(tbe_s* h, const float* d_grad_out, float lr, 
     a.T = h->T;
     a.sumD = (int32_t)h->sumD;
     a.dpad = (int32_t)align_up((size_t)h->dmax, 4);
-    a.lr = lr;
-    a.eps = eps;
+    a.opt.state0 = h->d_state;
+    a.opt.state1 = h->optimizer == TBE_OPT_ADAM ? h->d_state + h->weight_elems : h->d_state;
+    a.opt.lr = oc.lr;
+    a.opt.eps = oc.eps;
+    a.opt.beta1 = oc.beta1;
+    a.opt.beta2 = oc.beta2;
+    a.opt.inv_bc1 = 1.0f;
+    a.opt.inv_bc2 = 1.0f;
+    if (h->optimizer == TBE_OPT_ADAM) {
+        // bias corrections in double from the float32 betas the kernel uses
+        a.opt.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)oc.beta1, (double)oc.step)));
+        a.opt.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)oc.beta2, (double)oc.step)));
+    }
     const int per_block = kBwdThreads / kWave;
-    {
-        ScopedTimer tm(h, SLOT_REDUCE_UPDATE, st);
-        const dim3 grid((unsigned)ceil_div(num_chunks, per_block)), block(kBwdThreads);
-        if (h->dtype == TBE_DTYPE_FP32)
-            hipLaunchKernelGGL(reduce_update_kernel<float>, grid, block, 0, st, a);
-        else
-            hipLaunchKernelGGL(reduce_update_kernel<__half>, grid, block, 0, st, a);
-        TBE_LAUNCH_CHECK(h, "reduce_update_kernel");
-    }
-    {
-        ScopedTimer tm(h, SLOT_LONG_FIXUP, st);
-        const int64_t max_long = n / kLongRun + 1;
-        const dim3 grid((unsigned)std::min<int64_t>(2048, ceil_div(max_long, per_block))), block(kBwdThreads);
-        if (h->dtype == TBE_DTYPE_FP32)
-            hipLaunchKernelGGL(long_run_fixup_kernel<float>, grid, block, 0, st, a);
-        else
-            hipLaunchKernelGGL(long_run_fixup_kernel<__half>, grid, block, 0, st, a);
-        TBE_LAUNCH_CHECK(h, "long_run_fixup_kernel");
-    }
+    const dim3 grid((unsigned)ceil_div(num_chunks, per_block));
+    const int64_t max_long = n / kLongRun + 1;
+    const dim3 grid_fix((unsigned)std::min<int64_t>(2048, ceil_div(max_long, per_block)));
+    if (h->dtype == TBE_DTYPE_FP32)
+        launch_update_grad<float>(a, grid, grid_fix, st, h);
+    else
+        launch_update_grad<__half>(a, grid, grid_fix, st, h);
+    TBE_LAUNCH_CHECK(h, "reduce_update / long_run_fixup kernels");
     return TBE_OK;
 }
 
@@ -602,23 +668,38 @@ tbe_status_t tbe_backward_sort(tbe_handle_t h, const int32_t* d_indices, const i
     return enqueue_sort(h, d_indices, d_offsets, (int32_t)num_indices, batch, static_cast<hipStream_t>(stream));
 }
 
-tbe_status_t tbe_backward_update_rowwise_adagrad(tbe_handle_t h, const float* d_grad_out, float lr, float eps,
-                                                 void* stream)
+static tbe_status_t check_opt(tbe_s* h, const OptCall& oc)
 {
     if (!h)
         return TBE_ERR_INVALID_ARG;
     if (!h->bound)
         return TBE_ERR_NOT_BOUND;
-    if (h->final_buf < 0 || h->sorted_n < 0)
+    if (h->optimizer != oc.optimizer)
         return TBE_ERR_INVALID_ARG;
-    return enqueue_update(h, d_grad_out, lr, eps, static_cast<hipStream_t>(stream));
+    if (oc.optimizer == TBE_OPT_ADAM &&
+        (oc.step < 1 || !(oc.beta1 >= 0.f && oc.beta1 < 1.f) || !(oc.beta2 >= 0.f && oc.beta2 < 1.f)))
+        return TBE_ERR_INVALID_ARG;
+    return TBE_OK;
 }
 
-tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
-                                          const int64_t* d_offsets, int64_t num_indices, int32_t batch,
-                                          const float* d_grad_out, float lr, float eps, void* stream)
+static tbe_status_t backward_update(tbe_handle_t h, const void* d_grad_out, const OptCall& oc, void* stream)
+{
+    tbe_status_t rc = check_opt(h, oc);
+    if (rc != TBE_OK)
+        return rc;
+    if (h->final_buf < 0 || h->sorted_n < 0)
+        return TBE_ERR_INVALID_ARG;
+    return enqueue_update(h, d_grad_out, oc, static_cast<hipStream_t>(stream));
+}
+
+static tbe_status_t backward_full(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                                  int64_t num_indices, int32_t batch, const void* d_grad_out, const OptCall& oc,
+                                  void* stream)
 {
     tbe_status_t rc = check_call(h, d_indices, d_offsets, num_indices, batch);
+    if (rc != TBE_OK)
+        return rc;
+    rc = check_opt(h, oc);
     if (rc != TBE_OK)
         return rc;
     if (batch > 0 && num_indices > 0 && !d_grad_out)
@@ -627,7 +708,48 @@ tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indic
     rc = enqueue_sort(h, d_indices, d_offsets, (int32_t)num_indices, batch, st);
     if (rc != TBE_OK)
         return rc;
-    return enqueue_update(h, d_grad_out, lr, eps, st);
+    return enqueue_update(h, d_grad_out, oc, st);
+}
+
+tbe_status_t tbe_backward_update_rowwise_adagrad(tbe_handle_t h, const void* d_grad_out, float lr, float eps,
+                                                 void* stream)
+{
+    return backward_update(h, d_grad_out, OptCall{TBE_OPT_ROWWISE_ADAGRAD, lr, eps, 0.f, 0.f, 1}, stream);
+}
+
+tbe_status_t tbe_backward_update_adagrad(tbe_handle_t h, const void* d_grad_out, float lr, float eps, void* stream)
+{
+    return backward_update(h, d_grad_out, OptCall{TBE_OPT_ADAGRAD, lr, eps, 0.f, 0.f, 1}, stream);
+}
+
+tbe_status_t tbe_backward_update_adam(tbe_handle_t h, const void* d_grad_out, float lr, float beta1, float beta2,
+                                      float eps, int64_t step, void* stream)
+{
+    return backward_update(h, d_grad_out, OptCall{TBE_OPT_ADAM, lr, eps, beta1, beta2, step}, stream);
+}
+
+tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                                          int64_t num_indices, int32_t batch, const void* d_grad_out, float lr,
+                                          float eps, void* stream)
+{
+    return backward_full(h, d_indices, d_offsets, num_indices, batch, d_grad_out,
+                         OptCall{TBE_OPT_ROWWISE_ADAGRAD, lr, eps, 0.f, 0.f, 1}, stream);
+}
+
+tbe_status_t tbe_backward_adagrad(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                                  int64_t num_indices, int32_t batch, const void* d_grad_out, float lr, float eps,
+                                  void* stream)
+{
+    return backward_full(h, d_indices, d_offsets, num_indices, batch, d_grad_out,
+                         OptCall{TBE_OPT_ADAGRAD, lr, eps, 0.f, 0.f, 1}, stream);
+}
+
+tbe_status_t tbe_backward_adam(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
+                               int64_t num_indices, int32_t batch, const void* d_grad_out, float lr, float beta1,
+                               float beta2, float eps, int64_t step, void* stream)
+{
+    return backward_full(h, d_indices, d_offsets, num_indices, batch, d_grad_out,
+                         OptCall{TBE_OPT_ADAM, lr, eps, beta1, beta2, step}, stream);
 }
 
 tbe_status_t tbe_backward_artifacts(tbe_handle_t h, const uint32_t** d_sorted_keys,

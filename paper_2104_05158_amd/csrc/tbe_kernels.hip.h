@@ -10,6 +10,7 @@
 // fetch different rows at the same time; sums across groups and across a row use xor-shuffles.
 #pragma once
 
+#include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -143,11 +144,24 @@ struct RowIO<__half, 8> {
 // end of a bag read a row of zeros kept in the workspace (pointer select instead of a predicated
 // load), column offsets past D are clamped (those lanes never store), and the indices of the next
 // step are requested before the rows of the current step are consumed.
-template <typename WT, int EPL, int KMAX>
+// 4 pooled values in the output type OT (float, or __half rounded to nearest even)
+__device__ __forceinline__ void store_out4(float* p, float a, float b, float c, float d)
+{
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+__device__ __forceinline__ void store_out4(__half* p, float a, float b, float c, float d)
+{
+    uint2 v;
+    *reinterpret_cast<__half2*>(&v.x) = __floats2half2_rn(a, b);
+    *reinterpret_cast<__half2*>(&v.y) = __floats2half2_rn(c, d);
+    *reinterpret_cast<uint2*>(p) = v;
+}
+
+template <typename WT, int EPL, int KMAX, typename OT>
 __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
     const TableMeta* __restrict__ meta, const WT* __restrict__ weights,
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
-    float* __restrict__ out, const void* __restrict__ zero_row, int32_t B, int32_t num_bags,
+    OT* __restrict__ out, const void* __restrict__ zero_row, int32_t B, int32_t num_bags,
     int32_t sumD, int32_t n_total, int32_t bags_per_wave)
 {
     using IO = RowIO<WT, EPL>;
@@ -227,14 +241,13 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
 
         if (active) {
             const int b = j - t * B + grp;
-            float* op = out + (int64_t)b * sumD + m.col;
+            OT* op = out + (int64_t)b * sumD + m.col;
 #pragma unroll
             for (int k = 0; k < KMAX; ++k) {
                 if (evalid[k]) {
 #pragma unroll
                     for (int q = 0; q < EPL; q += 4)
-                        *reinterpret_cast<float4*>(op + eoff[k] + q) =
-                            make_float4(acc[k][q], acc[k][q + 1], acc[k][q + 2], acc[k][q + 3]);
+                        store_out4(op + eoff[k] + q, acc[k][q], acc[k][q + 1], acc[k][q + 2], acc[k][q + 3]);
                 }
             }
         }
@@ -821,6 +834,25 @@ __device__ __forceinline__ int find_table(const uint32_t* __restrict__ row_base,
     return a;
 }
 
+// Optimizer of the fused epilogue (Section 5.1 names AdaGrad and Adam next to the row-wise AdaGrad of
+// Section 5.2).  state0: row-wise AdaGrad -> one moment per row (indexed by linear row id);
+// AdaGrad -> sum of squares per element; Adam -> first moment per element, state1 -> second moment.
+// Per-element states are indexed like the flat weight array.
+constexpr int kOptRowwiseAdagrad = 0;
+constexpr int kOptAdagrad = 1;
+constexpr int kOptAdam = 2;
+
+struct OptParams {
+    float* state0;
+    float* state1;
+    float lr;
+    float eps;
+    float beta1;
+    float beta2;
+    float inv_bc1;   // 1 / (1 - beta1^step)
+    float inv_bc2;   // 1 / (1 - beta2^step)
+};
+
 struct BwdArgs {
     const TableMeta* meta;
     const uint32_t* row_base;
@@ -830,9 +862,8 @@ struct BwdArgs {
     const int32_t* seg_offsets;
     const int32_t* chunk_first_run;
     Counters* counters;
-    const float* grad_out;
+    const void* grad_out;   // [B, sumD] in the gradient type (float, __half or __hip_bfloat16)
     void* weights;
-    float* moments;
     float* partials;      // [num_chunks][2][dpad]
     uint32_t* long_list;
     const float* zero_row;  // >= 2 KiB of zeros
@@ -841,8 +872,7 @@ struct BwdArgs {
     int32_t T;
     int32_t sumD;
     int32_t dpad;
-    float lr;
-    float eps;
+    OptParams opt;
 };
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
@@ -851,7 +881,37 @@ __device__ __forceinline__ void acc4(float (&a)[4], const float4 v)
     a[0] += v.x; a[1] += v.y; a[2] += v.z; a[3] += v.w;
 }
 
-// Per-lane column geometry of a D-float row covered by LPR lanes with two float4 blocks each.
+// Gradient rows in their storage type: Vec is what one lane loads for a block of 4 elements.
+template <typename GT>
+struct GradIO;
+
+template <>
+struct GradIO<float> {
+    using Vec = float4;
+    __device__ static __forceinline__ Vec ldv(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    __device__ static __forceinline__ void add(float (&a)[4], const Vec v) { acc4(a, v); }
+};
+
+template <>
+struct GradIO<__half> {
+    using Vec = uint2;
+    __device__ static __forceinline__ Vec ldv(const __half* p) { return *reinterpret_cast<const uint2*>(p); }
+    __device__ static __forceinline__ void add(float (&a)[4], const Vec v) { RowIO<__half, 4>::add(a, v); }
+};
+
+template <>
+struct GradIO<__hip_bfloat16> {
+    using Vec = uint2;
+    __device__ static __forceinline__ Vec ldv(const __hip_bfloat16* p) { return *reinterpret_cast<const uint2*>(p); }
+    // bfloat16 is the upper half of a float: widening is a 16-bit shift
+    __device__ static __forceinline__ void add(float (&a)[4], const Vec v)
+    {
+        a[0] += __uint_as_float(v.x << 16); a[1] += __uint_as_float(v.x & 0xffff0000u);
+        a[2] += __uint_as_float(v.y << 16); a[3] += __uint_as_float(v.y & 0xffff0000u);
+    }
+};
+
+// Per-lane column geometry of a D-element row covered by LPR lanes with two 4-element blocks each.
 struct Cols {
     int e0, e1;      // clamped element offsets of the two blocks (always loadable)
     bool c0, c1;     // whether the block really belongs to the row
@@ -869,12 +929,14 @@ struct Cols {
     }
 };
 
-// Whole-wavefront sum of the fp32 rows rowptr(i), i in [p0, p1), p1 > p0; rowptr must be valid for
-// every i in the range.  Afterwards every lane group holds the complete sums.
-template <typename RowPtr>
-__device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, const float* __restrict__ zero_row,
+// Whole-wavefront fp32 sum of the rows rowptr(i) (element type GT), i in [p0, p1), p1 > p0; rowptr must
+// be valid for every i in the range.  Afterwards every lane group holds the complete sums.
+template <typename GT, typename RowPtr>
+__device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, const float* __restrict__ zero_row_f,
                                                 const Cols& c, float (&acc)[2][4])
 {
+    using GIO = GradIO<GT>;
+    const GT* zero_row = reinterpret_cast<const GT*>(zero_row_f);
     const int G = kWave >> c.lprl;
 #pragma unroll
     for (int k = 0; k < 2; ++k)
@@ -882,23 +944,23 @@ __device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, c
         for (int e = 0; e < 4; ++e)
             acc[k][e] = 0.f;
     for (int i0 = p0; i0 < p1; i0 += G * kBwdUnroll) {
-        float4 v[kBwdUnroll][2];
-        const float* rp[kBwdUnroll];
+        typename GIO::Vec v[kBwdUnroll][2];
+        const GT* rp[kBwdUnroll];
 #pragma unroll
         for (int u = 0; u < kBwdUnroll; ++u) {
             const int i = i0 + u * G + c.grp;
-            const float* p = rowptr(min(i, p1 - 1));
+            const GT* p = rowptr(min(i, p1 - 1));
             rp[u] = i < p1 ? p : zero_row;
         }
 #pragma unroll
         for (int u = 0; u < kBwdUnroll; ++u) {
-            v[u][0] = ld4(rp[u] + c.e0);
-            v[u][1] = ld4(rp[u] + c.e1);
+            v[u][0] = GIO::ldv(rp[u] + c.e0);
+            v[u][1] = GIO::ldv(rp[u] + c.e1);
         }
 #pragma unroll
         for (int u = 0; u < kBwdUnroll; ++u) {
-            acc4(acc[0], v[u][0]);
-            acc4(acc[1], v[u][1]);
+            GIO::add(acc[0], v[u][0]);
+            GIO::add(acc[1], v[u][1]);
         }
     }
     for (int s = 1 << c.lprl; s < kWave; s <<= 1) {
@@ -910,39 +972,114 @@ __device__ __forceinline__ void wave_gather_sum(RowPtr rowptr, int p0, int p1, c
     }
 }
 
-// The AdaGrad epilogue for the row held by this lane's group (wv: the row's old values, raw).
-template <typename WT>
-__device__ __forceinline__ void adagrad_epilogue(WT* __restrict__ wrow, float* __restrict__ mptr, float m_old,
-                                                 const typename RowIO<WT, 4>::Vec (&wv)[2],
-                                                 const float (&acc)[2][4], int D, const Cols& c, bool writer,
-                                                 float lr, float eps)
+// The optimizer state of the row held by this lane's group, requested together with the row itself.
+template <int OPT>
+struct OptRow {
+    float m_old;         // row-wise AdaGrad
+    float4 s0[2];        // AdaGrad sum of squares / Adam first moment, this lane's two blocks
+    float4 s1[2];        // Adam second moment
+    // key: linear row id; wel: index of the row's first element in the flat weight array
+    __device__ __forceinline__ void load(const OptParams& p, uint32_t key, int64_t wel, const Cols& c)
+    {
+        if (OPT == kOptRowwiseAdagrad)
+            m_old = p.state0[key];
+        if (OPT == kOptAdagrad || OPT == kOptAdam) {
+            s0[0] = ld4(p.state0 + wel + c.e0);
+            s0[1] = ld4(p.state0 + wel + c.e1);
+        }
+        if (OPT == kOptAdam) {
+            s1[0] = ld4(p.state1 + wel + c.e0);
+            s1[1] = ld4(p.state1 + wel + c.e1);
+        }
+    }
+};
+
+__device__ __forceinline__ void st4(float* p, const float (&f)[4])
 {
-    float ss0 = acc[0][0] * acc[0][0] + acc[0][1] * acc[0][1] + acc[0][2] * acc[0][2] + acc[0][3] * acc[0][3];
-    float ss1 = acc[1][0] * acc[1][0] + acc[1][1] * acc[1][1] + acc[1][2] * acc[1][2] + acc[1][3] * acc[1][3];
-    float ss = (c.c0 ? ss0 : 0.f) + (c.c1 ? ss1 : 0.f);
-    for (int s = 1; s < (1 << c.lprl); s <<= 1)
-        ss += __shfl_xor(ss, s);
-    // hardware reciprocal / square root (1 ulp each): far inside the 1e-5 tolerance of the result
-    const float m_new = m_old + ss * __builtin_amdgcn_rcpf((float)D);
-    const float scale = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(m_new) + eps);
-    if (writer) {
+    *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+}
+__device__ __forceinline__ void un4(const float4 v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+
+// One block (4 elements) of the element-wise rules; g: aggregated gradient, w: weights (updated in place).
+// Hardware reciprocal / square root (1 ulp each): far inside the 1e-5 tolerance of the result.
+template <int OPT>
+__device__ __forceinline__ void elementwise_block(const OptParams& p, const float (&g)[4], float (&w)[4],
+                                                  const float4 s0v, const float4 s1v, float* s0p, float* s1p)
+{
+    float a[4], b[4];
+    un4(s0v, a);
+    if (OPT == kOptAdagrad) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] += g[e] * g[e];
+            w[e] -= p.lr * g[e] * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(a[e]) + p.eps);
+        }
+        st4(s0p, a);
+    } else {
+        un4(s1v, b);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = p.beta1 * a[e] + (1.0f - p.beta1) * g[e];
+            b[e] = p.beta2 * b[e] + (1.0f - p.beta2) * g[e] * g[e];
+            w[e] -= p.lr * (a[e] * p.inv_bc1) *
+                    __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(b[e] * p.inv_bc2) + p.eps);
+        }
+        st4(s0p, a);
+        st4(s1p, b);
+    }
+}
+
+// The optimizer epilogue for the row held by this lane's group (wv: the row's old values, raw).
+//   row-wise AdaGrad (Section 5.2): m += mean_d(G_d^2); w -= lr * G / (sqrt(m) + eps)
+//   AdaGrad: S_d += G_d^2; w_d -= lr * G_d / (sqrt(S_d) + eps)
+//   Adam (lazy, bias-corrected): m = b1 m + (1-b1) G; v = b2 v + (1-b2) G^2;
+//                                w -= lr * (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps)
+template <typename WT, int OPT>
+__device__ __forceinline__ void optimizer_epilogue(WT* __restrict__ wrow, const typename RowIO<WT, 4>::Vec (&wv)[2],
+                                                   const float (&acc)[2][4], int D, const Cols& c, bool writer,
+                                                   const OptParams& p, uint32_t key, int64_t wel,
+                                                   const OptRow<OPT>& st)
+{
+    if (OPT == kOptRowwiseAdagrad) {
+        float ss0 = acc[0][0] * acc[0][0] + acc[0][1] * acc[0][1] + acc[0][2] * acc[0][2] + acc[0][3] * acc[0][3];
+        float ss1 = acc[1][0] * acc[1][0] + acc[1][1] * acc[1][1] + acc[1][2] * acc[1][2] + acc[1][3] * acc[1][3];
+        float ss = (c.c0 ? ss0 : 0.f) + (c.c1 ? ss1 : 0.f);
+        for (int s = 1; s < (1 << c.lprl); s <<= 1)
+            ss += __shfl_xor(ss, s);
+        // hardware reciprocal / square root (1 ulp each): far inside the 1e-5 tolerance of the result
+        const float m_new = st.m_old + ss * __builtin_amdgcn_rcpf((float)D);
+        const float scale = p.lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(m_new) + p.eps);
+        if (writer) {
+            float w[4];
+            if (c.c0) {
+                RowIO<WT, 4>::unpack(wv[0], w);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] -= scale * acc[0][e];
+                RowIO<WT, 4>::store(wrow + c.e0, w);
+            }
+            if (c.c1) {
+                RowIO<WT, 4>::unpack(wv[1], w);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] -= scale * acc[1][e];
+                RowIO<WT, 4>::store(wrow + c.e1, w);
+            }
+            if (c.sub == 0)
+                p.state0[key] = m_new;
+        }
+    } else if (writer) {
         float w[4];
         if (c.c0) {
             RowIO<WT, 4>::unpack(wv[0], w);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                w[e] -= scale * acc[0][e];
+            elementwise_block<OPT>(p, acc[0], w, st.s0[0], st.s1[0], p.state0 + wel + c.e0, p.state1 + wel + c.e0);
             RowIO<WT, 4>::store(wrow + c.e0, w);
         }
         if (c.c1) {
             RowIO<WT, 4>::unpack(wv[1], w);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                w[e] -= scale * acc[1][e];
+            elementwise_block<OPT>(p, acc[1], w, st.s0[1], st.s1[1], p.state0 + wel + c.e1, p.state1 + wel + c.e1);
             RowIO<WT, 4>::store(wrow + c.e1, w);
         }
-        if (c.sub == 0)
-            *mptr = m_new;
     }
 }
 
@@ -957,29 +1094,33 @@ __device__ __forceinline__ void store_partial(float* __restrict__ dst, const flo
 }
 
 // G short runs at once, one per lane group; ML = longest run of the batch (1..kShortRun).
-template <typename WT, int ML>
-__device__ __forceinline__ void short_batch(const BwdArgs& a, WT* __restrict__ wtab, const float* __restrict__ gb,
-                                            const int32_t* __restrict__ s_val, int q0, int s, int len,
-                                            uint32_t key, uint32_t rbase, int D, const Cols& c, bool active)
+template <typename WT, typename GT, int OPT, int ML>
+__device__ __forceinline__ void short_batch(const BwdArgs& a, WT* __restrict__ wtab, int64_t woff,
+                                            const GT* __restrict__ gb, const int32_t* __restrict__ s_val, int q0,
+                                            int s, int len, uint32_t key, uint32_t rbase, int D, const Cols& c,
+                                            bool active)
 {
     using IO = RowIO<WT, 4>;
+    using GIO = GradIO<GT>;
     const int64_t sumD = a.sumD;
-    WT* wrow = wtab + (int64_t)(key - rbase) * D;          // key is a valid row even for idle groups
+    const int64_t rel = (int64_t)(key - rbase) * D;        // key is a valid row even for idle groups
+    WT* wrow = wtab + rel;
     typename IO::Vec wv[2];
     wv[0] = IO::ldv(wrow + c.e0);
     wv[1] = IO::ldv(wrow + c.e1);
-    const float m_old = a.moments[key];
-    const float* rp[ML];
+    OptRow<OPT> st;
+    st.load(a.opt, key, woff + rel, c);
+    const GT* rp[ML];
 #pragma unroll
     for (int u = 0; u < ML; ++u) {
         const int b = s_val[s - q0 + (u < len ? u : 0)];
-        rp[u] = (active && u < len) ? gb + (int64_t)b * sumD : a.zero_row;
+        rp[u] = (active && u < len) ? gb + (int64_t)b * sumD : reinterpret_cast<const GT*>(a.zero_row);
     }
-    float4 v[ML][2];
+    typename GIO::Vec v[ML][2];
 #pragma unroll
     for (int u = 0; u < ML; ++u) {
-        v[u][0] = ld4(rp[u] + c.e0);
-        v[u][1] = ld4(rp[u] + c.e1);
+        v[u][0] = GIO::ldv(rp[u] + c.e0);
+        v[u][1] = GIO::ldv(rp[u] + c.e1);
     }
     float acc[2][4];
 #pragma unroll
@@ -989,16 +1130,17 @@ __device__ __forceinline__ void short_batch(const BwdArgs& a, WT* __restrict__ w
             acc[k][e] = 0.f;
 #pragma unroll
     for (int u = 0; u < ML; ++u) {
-        acc4(acc[0], v[u][0]);
-        acc4(acc[1], v[u][1]);
+        GIO::add(acc[0], v[u][0]);
+        GIO::add(acc[1], v[u][1]);
     }
-    adagrad_epilogue<WT>(wrow, a.moments + key, m_old, wv, acc, D, c, active, a.lr, a.eps);
+    optimizer_epilogue<WT, OPT>(wrow, wv, acc, D, c, active, a.opt, key, woff + rel, st);
 }
 
-template <typename WT>
+template <typename WT, typename GT, int OPT>
 __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
 {
     using IO = RowIO<WT, 4>;
+    const GT* __restrict__ grad_out = static_cast<const GT*>(a.grad_out);
     constexpr int kWaves = kBwdThreads / kWave;
     constexpr int kSegCap = 3 * kWave;             // >= kChunk + 1
     constexpr int kValCap = kChunk + kLongRun;     // a run owned by the chunk ends within this window
@@ -1086,10 +1228,10 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         const int e0 = a.seg_offsets[u0 + 1];
         if (e0 - s0 > kLongRun) {
             seek_table(a.unique_keys[u0]);
-            const float* gb = a.grad_out + m.col;
+            const GT* gb = grad_out + m.col;
             const Cols c(m.dim, m.lpr_bwd, lane);
-            wave_gather_sum([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, q0, min(e0, q1), a.zero_row,
-                            c, acc);
+            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, q0, min(e0, q1),
+                                a.zero_row, c, acc);
             store_partial(a.partials + ((int64_t)k * 2 + 0) * a.dpad, acc, c);
         }
     }
@@ -1102,21 +1244,26 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         const int lprl = m.lpr_bwd;
         const int s0 = uniform(s_seg[r]);
         const int len0 = uniform(s_seg[r + 1]) - s0;
-        const float* gb = a.grad_out + m.col;
+        const GT* gb = grad_out + m.col;
         WT* wtab = weights + m.woff;
         const Cols c(D, lprl, lane);
         if (len0 > kShortRun) {
             // ---- one run, whole wavefront
-            WT* wrow = wtab + (int64_t)(key0 - m.rbase) * D;
+            const int64_t rel = (int64_t)(key0 - m.rbase) * D;
+            WT* wrow = wtab + rel;
             const bool is_long = len0 > kLongRun;
             typename IO::Vec wvv[2];
-            wvv[0] = IO::ldv(wrow + c.e0);
-            wvv[1] = IO::ldv(wrow + c.e1);
-            const float m_old = a.moments[key0];
-            const int e = is_long ? q1 : s0 + len0;
-            wave_gather_sum([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, s0, e, a.zero_row, c, acc);
+            OptRow<OPT> st;
             if (!is_long) {
-                adagrad_epilogue<WT>(wrow, a.moments + key0, m_old, wvv, acc, D, c, c.grp == 0, a.lr, a.eps);
+                wvv[0] = IO::ldv(wrow + c.e0);
+                wvv[1] = IO::ldv(wrow + c.e1);
+                st.load(a.opt, key0, m.woff + rel, c);
+            }
+            const int e = is_long ? q1 : s0 + len0;
+            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, s0, e, a.zero_row, c,
+                                acc);
+            if (!is_long) {
+                optimizer_epilogue<WT, OPT>(wrow, wvv, acc, D, c, c.grp == 0, a.opt, key0, m.woff + rel, st);
             } else {
                 store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, c);
                 if (lane == 0) {
@@ -1145,10 +1292,10 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
                            (__ballot(lenc > 3) != 0ull);
             static_assert(kShortRun == 4, "short_batch is instantiated for 1..4 lookups");
             switch (ml) {
-                case 1: short_batch<WT, 1>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                case 2: short_batch<WT, 2>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                case 3: short_batch<WT, 3>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                default: short_batch<WT, 4>(a, wtab, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 1: short_batch<WT, GT, OPT, 1>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 2: short_batch<WT, GT, OPT, 2>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 3: short_batch<WT, GT, OPT, 3>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                default: short_batch<WT, GT, OPT, 4>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
             }
             r += nb;
         }
@@ -1158,7 +1305,7 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
 // One wavefront per queued long run: adds the per-chunk partial rows in chunk order (first the
 // piece written by the chunk where the run starts, then one piece per following chunk) and applies
 // the run's single AdaGrad step.
-template <typename WT>
+template <typename WT, int OPT>
 __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
 {
     using IO = RowIO<WT, 4>;
@@ -1180,14 +1327,16 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
         const int k1 = (e - 1) / kChunk;
         const float* pbase = a.partials;
         const int64_t dpad = a.dpad;
-        WT* wrow = weights + m.woff + (int64_t)(key - m.rbase) * m.dim;
+        const int64_t wel = m.woff + (int64_t)(key - m.rbase) * m.dim;
+        WT* wrow = weights + wel;
         typename IO::Vec wvv[2];
         wvv[0] = IO::ldv(wrow + c.e0);
         wvv[1] = IO::ldv(wrow + c.e1);
-        const float m_old = a.moments[key];
-        wave_gather_sum([&](int cc) { return pbase + ((int64_t)(k0 + cc) * 2 + (cc == 0 ? 1 : 0)) * dpad; }, 0,
-                        k1 - k0 + 1, a.zero_row, c, acc);
-        adagrad_epilogue<WT>(wrow, a.moments + key, m_old, wvv, acc, m.dim, c, c.grp == 0, a.lr, a.eps);
+        OptRow<OPT> st;
+        st.load(a.opt, key, wel, c);
+        wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + cc) * 2 + (cc == 0 ? 1 : 0)) * dpad; },
+                               0, k1 - k0 + 1, a.zero_row, c, acc);
+        optimizer_epilogue<WT, OPT>(wrow, wvv, acc, m.dim, c, c.grp == 0, a.opt, key, wel, st);
     }
 }
 

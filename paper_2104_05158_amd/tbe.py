@@ -25,11 +25,17 @@ TBE_ERR_INDEX_OUT_OF_RANGE = 5
 TBE_ERR_HIP = 6
 TBE_DTYPE_FP32 = 0
 TBE_DTYPE_FP16 = 1
+TBE_DTYPE_BF16 = 2
 TBE_POOLING_SUM = 0
+TBE_OPT_ROWWISE_ADAGRAD = 0
+TBE_OPT_ADAGRAD = 1
+TBE_OPT_ADAM = 2
+_TORCH_DTYPE = {TBE_DTYPE_FP32: torch.float32, TBE_DTYPE_FP16: torch.float16, TBE_DTYPE_BF16: torch.bfloat16}
 
 EXPORTED = [
     "tbe_create", "tbe_destroy", "tbe_query_sizes", "tbe_bind", "tbe_forward",
-    "tbe_backward_rowwise_adagrad", "tbe_backward_sort", "tbe_backward_update_rowwise_adagrad",
+    "tbe_backward_rowwise_adagrad", "tbe_backward_adagrad", "tbe_backward_adam", "tbe_backward_sort",
+    "tbe_backward_update_rowwise_adagrad", "tbe_backward_update_adagrad", "tbe_backward_update_adam",
     "tbe_backward_artifacts", "tbe_check_inputs",
     "tbe_profile_enable", "tbe_profile_read", "tbe_status_string", "tbe_last_hip_error",
 ]
@@ -54,6 +60,10 @@ class tbe_config_t(ctypes.Structure):
         ("pooling", ctypes.c_int32),
         ("max_batch", ctypes.c_int32),
         ("max_indices", ctypes.c_int64),
+        ("optimizer", ctypes.c_int32),
+        ("output_dtype", ctypes.c_int32),
+        ("grad_dtype", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 
@@ -75,8 +85,12 @@ def lib() -> ctypes.CDLL:
         L.tbe_bind.argtypes = [vp, vp, vp, vp, ctypes.c_size_t]
         L.tbe_forward.argtypes = [vp, vp, vp, i64, i32, vp, vp]
         L.tbe_backward_rowwise_adagrad.argtypes = [vp, vp, vp, i64, i32, vp, f32, f32, vp]
+        L.tbe_backward_adagrad.argtypes = [vp, vp, vp, i64, i32, vp, f32, f32, vp]
+        L.tbe_backward_adam.argtypes = [vp, vp, vp, i64, i32, vp, f32, f32, f32, f32, i64, vp]
         L.tbe_backward_sort.argtypes = [vp, vp, vp, i64, i32, vp]
         L.tbe_backward_update_rowwise_adagrad.argtypes = [vp, vp, f32, f32, vp]
+        L.tbe_backward_update_adagrad.argtypes = [vp, vp, f32, f32, vp]
+        L.tbe_backward_update_adam.argtypes = [vp, vp, f32, f32, f32, f32, i64, vp]
         L.tbe_backward_artifacts.argtypes = [vp] + [ctypes.POINTER(vp)] * 5
         L.tbe_check_inputs.argtypes = [vp, vp, vp, i64, i32, vp]
         L.tbe_profile_enable.argtypes = [vp, i32]
@@ -115,12 +129,14 @@ def _stream_ptr(stream) -> ctypes.c_void_p:
 # ---- raw calls, one per C entry point (return the status; raise nothing) ----
 
 def tbe_create(rows, dims, weight_dtype: int, max_batch: int, max_indices: int,
-               pooling: int = TBE_POOLING_SUM) -> Tuple[int, Optional[int]]:
+               pooling: int = TBE_POOLING_SUM, optimizer: int = TBE_OPT_ROWWISE_ADAGRAD,
+               output_dtype: int = TBE_DTYPE_FP32, grad_dtype: int = TBE_DTYPE_FP32,
+               reserved: int = 0) -> Tuple[int, Optional[int]]:
     rows = np.ascontiguousarray(rows, np.int64)
     dims = np.ascontiguousarray(dims, np.int32)
     cfg = tbe_config_t(len(rows), rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                        dims.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), weight_dtype, pooling,
-                       max_batch, max_indices)
+                       max_batch, max_indices, optimizer, output_dtype, grad_dtype, reserved)
     h = ctypes.c_void_p()
     rc = lib().tbe_create(ctypes.byref(cfg), ctypes.byref(h))
     return rc, (h.value if rc == TBE_OK else None)
@@ -156,6 +172,28 @@ def tbe_backward_rowwise_adagrad(h, indices, offsets, num_indices: int, batch: i
                                  eps: float, stream=None) -> int:
     return lib().tbe_backward_rowwise_adagrad(ctypes.c_void_p(h), _ptr(indices), _ptr(offsets), num_indices,
                                               batch, _ptr(grad_out), lr, eps, _stream_ptr(stream))
+
+
+def tbe_backward_adagrad(h, indices, offsets, num_indices: int, batch: int, grad_out, lr: float, eps: float,
+                         stream=None) -> int:
+    return lib().tbe_backward_adagrad(ctypes.c_void_p(h), _ptr(indices), _ptr(offsets), num_indices, batch,
+                                      _ptr(grad_out), lr, eps, _stream_ptr(stream))
+
+
+def tbe_backward_adam(h, indices, offsets, num_indices: int, batch: int, grad_out, lr: float, beta1: float,
+                      beta2: float, eps: float, step: int, stream=None) -> int:
+    return lib().tbe_backward_adam(ctypes.c_void_p(h), _ptr(indices), _ptr(offsets), num_indices, batch,
+                                   _ptr(grad_out), lr, beta1, beta2, eps, step, _stream_ptr(stream))
+
+
+def tbe_backward_update_adagrad(h, grad_out, lr: float, eps: float, stream=None) -> int:
+    return lib().tbe_backward_update_adagrad(ctypes.c_void_p(h), _ptr(grad_out), lr, eps, _stream_ptr(stream))
+
+
+def tbe_backward_update_adam(h, grad_out, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                             stream=None) -> int:
+    return lib().tbe_backward_update_adam(ctypes.c_void_p(h), _ptr(grad_out), lr, beta1, beta2, eps, step,
+                                          _stream_ptr(stream))
 
 
 def tbe_backward_sort(h, indices, offsets, num_indices: int, batch: int, stream=None) -> int:
@@ -242,13 +280,18 @@ class TableBatchedEmbeddingBags:
     """Convenience owner of one handle and its device buffers (allocation is torch's, compute is the library's)."""
 
     def __init__(self, rows, dims, weight_dtype: int, max_batch: int, max_indices: int, device="cuda:0",
-                 weights: Optional[torch.Tensor] = None):
+                 weights: Optional[torch.Tensor] = None, optimizer: int = TBE_OPT_ROWWISE_ADAGRAD,
+                 output_dtype: int = TBE_DTYPE_FP32, grad_dtype: int = TBE_DTYPE_FP32):
         self.rows = np.ascontiguousarray(rows, np.int64)
         self.dims = np.ascontiguousarray(dims, np.int32)
         self.T = len(self.rows)
         self.weight_dtype = weight_dtype
+        self.optimizer = optimizer
+        self.out_torch_dtype = _TORCH_DTYPE[output_dtype]
+        self.grad_torch_dtype = _TORCH_DTYPE[grad_dtype]
         self.device = torch.device(device)
-        rc, h = tbe_create(self.rows, self.dims, weight_dtype, max_batch, max_indices)
+        rc, h = tbe_create(self.rows, self.dims, weight_dtype, max_batch, max_indices, optimizer=optimizer,
+                           output_dtype=output_dtype, grad_dtype=grad_dtype)
         if rc != TBE_OK:
             raise TbeError(rc, "tbe_create")
         self.h = h
@@ -284,7 +327,8 @@ class TableBatchedEmbeddingBags:
                 num_indices: Optional[int] = None):
         n = indices.numel() if num_indices is None else num_indices
         if out is None:
-            out = torch.empty(batch, self.sumD, dtype=torch.float32, device=self.device)
+            out = torch.empty(batch, self.sumD, dtype=self.out_torch_dtype, device=self.device)
+        assert out.dtype == self.out_torch_dtype and out.is_contiguous()
         rc = tbe_forward(self.h, indices, offsets, n, batch, out, stream)
         if rc != TBE_OK:
             raise TbeError(rc, "tbe_forward", tbe_last_hip_error(self.h))
@@ -294,9 +338,28 @@ class TableBatchedEmbeddingBags:
                                  stream=None, num_indices: Optional[int] = None):
         n = indices.numel() if num_indices is None else num_indices
         self._last_n = n
+        assert grad_out.dtype == self.grad_torch_dtype and grad_out.is_contiguous()
         rc = tbe_backward_rowwise_adagrad(self.h, indices, offsets, n, batch, grad_out, lr, eps, stream)
         if rc != TBE_OK:
             raise TbeError(rc, "tbe_backward_rowwise_adagrad", tbe_last_hip_error(self.h))
+
+    def backward_adagrad(self, indices, offsets, batch: int, grad_out, lr: float, eps: float, stream=None,
+                         num_indices: Optional[int] = None):
+        n = indices.numel() if num_indices is None else num_indices
+        self._last_n = n
+        assert grad_out.dtype == self.grad_torch_dtype and grad_out.is_contiguous()
+        rc = tbe_backward_adagrad(self.h, indices, offsets, n, batch, grad_out, lr, eps, stream)
+        if rc != TBE_OK:
+            raise TbeError(rc, "tbe_backward_adagrad", tbe_last_hip_error(self.h))
+
+    def backward_adam(self, indices, offsets, batch: int, grad_out, lr: float, beta1: float, beta2: float,
+                      eps: float, step: int, stream=None, num_indices: Optional[int] = None):
+        n = indices.numel() if num_indices is None else num_indices
+        self._last_n = n
+        assert grad_out.dtype == self.grad_torch_dtype and grad_out.is_contiguous()
+        rc = tbe_backward_adam(self.h, indices, offsets, n, batch, grad_out, lr, beta1, beta2, eps, step, stream)
+        if rc != TBE_OK:
+            raise TbeError(rc, "tbe_backward_adam", tbe_last_hip_error(self.h))
 
     def backward_sort(self, indices, offsets, batch: int, stream=None, num_indices: Optional[int] = None):
         n = indices.numel() if num_indices is None else num_indices

@@ -1,0 +1,187 @@
+"""GPU parity of the fused backward with element-wise AdaGrad and lazy sparse Adam, and of the 16-bit
+output / gradient types, against the CPU oracles (oracle/optimizers_oracle.py for the update rules,
+oracle/tbe_oracle.c for forward and aggregation), element by element through the C ABI.
+
+Tolerances: integer artefacts bit-exact; weights rtol 1e-5 (fp32 tables) / 2e-3 (fp16-stored) and
+optimizer states rtol 1e-5, each against the condition-aware scale of the quantity (sums of |terms|);
+untouched rows and their states bit-identical.  A float16 output adds one rounding of the fp32 sum:
+2^-11 relative (half an fp16 ulp is 2^-12) plus the fp16 subnormal step."""
+import numpy as np
+import pytest
+import torch
+
+import tbe_testlib as tl
+from oracle import optimizers_oracle as oo
+from oracle import tbe_oracle as orc
+from paper_2104_05158_amd import tbe
+from paper_2104_05158_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+LR, EPS, B1, B2 = 0.05, 1e-8, 0.9, 0.999
+
+
+def _round_grad(g: np.ndarray, grad_dtype: int) -> torch.Tensor:
+    """The gradient in its storage type; the float32 view of the SAME values feeds the oracle."""
+    t = torch.from_numpy(g)
+    return t.to(tbe._TORCH_DTYPE[grad_dtype])
+
+
+def _touched(spec, art):
+    R = np.concatenate([[0], np.cumsum(spec.rows)])
+    W = np.concatenate([[0], np.cumsum(spec.rows * spec.dims.astype(np.int64))])
+    keys = art.unique_keys.astype(np.int64)
+    t = np.searchsorted(R, keys, side="right") - 1
+    D = spec.dims.astype(np.int64)[t]
+    start = W[t] + (keys - R[t]) * D
+    elem = np.concatenate([np.arange(s, s + d) for s, d in zip(start, D)]) if len(keys) else np.zeros(0, np.int64)
+    return elem
+
+
+def _run(spec, optimizer, grad_dtype, device, steps=2, seed=0):
+    b = wl.make_batch(spec, "cpu", seed=seed + 1)
+    idx, off = b.indices.numpy(), b.offsets.numpy()
+    N, B = b.num_indices, spec.batch
+    w0 = wl.make_weights(spec, "cpu", seed=seed + 2).numpy()
+    rtol_w = tl.rtol_for(spec.dtype)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, max(N, 1), device=device,
+                                       weights=torch.from_numpy(w0.copy()).to(device), optimizer=optimizer,
+                                       grad_dtype=grad_dtype)
+    n_el = spec.weight_elems
+    assert op.state.numel() == (n_el if optimizer == tbe.TBE_OPT_ADAGRAD else 2 * n_el)
+    d_idx, d_off = torch.from_numpy(idx).to(device), torch.from_numpy(off).to(device)
+    art_ref = orc.sort_artifacts(spec.rows, B, idx, off)
+    elem = _touched(spec, art_ref)
+    touched = np.zeros(n_el, bool)
+    touched[elem] = True
+    w_ref = w0.copy()
+    s_ref = [np.zeros(n_el, np.float32), np.zeros(n_el, np.float32)]
+    for step in range(1, steps + 1):
+        g_t = _round_grad(wl.make_grad(spec, "cpu", seed=seed + 10 * step).numpy(), grad_dtype)
+        g32 = g_t.to(torch.float32).numpy()
+        w_prev, s_prev = w_ref.copy(), [x.copy() for x in s_ref]
+        _, goff, G, Gabs = oo.aggregated_gradients(spec.rows, spec.dims, spec.dtype, w_prev, idx, off, B, g32)
+        if optimizer == tbe.TBE_OPT_ADAGRAD:
+            oo.backward_adagrad(spec.rows, spec.dims, spec.dtype, w_ref, s_ref[0], idx, off, B, g32, LR, EPS)
+            op.backward_adagrad(d_idx, d_off, B, g_t.to(device), LR, EPS, num_indices=N)
+        else:
+            oo.backward_adam(spec.rows, spec.dims, spec.dtype, w_ref, s_ref[0], s_ref[1], idx, off, B, g32, LR, B1,
+                             B2, EPS, step)
+            op.backward_adam(d_idx, d_off, B, g_t.to(device), LR, B1, B2, EPS, step, num_indices=N)
+        tl.assert_artifacts_equal(op.artifacts(), art_ref, f"step {step}")
+        gw = op.weights.cpu().numpy()
+        gs = op.state.cpu().numpy()
+        gs = [gs[:n_el], gs[n_el:]] if optimizer == tbe.TBE_OPT_ADAM else [gs, None]
+        # ---- touched elements within tolerance (G and sum|terms| are laid out in touched-element order)
+        ga = Gabs
+        lr, eps = float(np.float32(LR)), float(np.float32(EPS))
+        wp = w_prev[elem].astype(np.float64)
+        if optimizer == tbe.TBE_OPT_ADAGRAD:
+            s_new = s_ref[0][elem].astype(np.float64)
+            scale_w = np.abs(wp) + lr * ga / (np.sqrt(s_new) + eps)
+            scale_s = [s_prev[0][elem].astype(np.float64) + ga * ga]
+        else:
+            b1, b2 = float(np.float32(B1)), float(np.float32(B2))
+            bc1, bc2 = 1 - b1 ** step, 1 - b2 ** step
+            m_hat = np.abs(s_ref[0][elem].astype(np.float64)) / bc1
+            v_hat = s_ref[1][elem].astype(np.float64) / bc2
+            scale_w = np.abs(wp) + lr * (m_hat + 2 * ga) / (np.sqrt(v_hat) + eps)
+            scale_s = [b1 * np.abs(s_prev[0][elem].astype(np.float64)) + (1 - b1) * ga,
+                       b2 * s_prev[1][elem].astype(np.float64) + (1 - b2) * ga * ga]
+        rel_w = np.abs(gw[elem].astype(np.float64) - w_ref[elem].astype(np.float64)) / (scale_w + 1e-300)
+        assert rel_w.max(initial=0.0) <= rtol_w, f"weights step {step}: rel err {rel_w.max():.3e}"
+        for k, sc in enumerate(scale_s):
+            rel_s = np.abs(gs[k][elem].astype(np.float64) - s_ref[k][elem].astype(np.float64)) / (sc + 1e-300)
+            assert rel_s.max(initial=0.0) <= tl.RTOL_FP32, f"state {k} step {step}: rel err {rel_s.max():.3e}"
+        # ---- everything else bit-identical
+        assert np.array_equal(gw[~touched].view(np.uint8), w0[~touched].view(np.uint8)), "untouched weights changed"
+        for k in range(len(scale_s)):
+            assert not gs[k][~touched].any(), "state of untouched rows changed"
+        # the next step starts from the GPU's own results on both sides (errors do not accumulate in the check)
+        w_ref = gw.copy()
+        s_ref = [gs[0].copy(), gs[1].copy() if gs[1] is not None else s_ref[1]]
+    op.close()
+
+
+SPECS = {
+    "mixed_small": lambda dt: wl.custom([300, 17, 2000, 64, 5], [128, 4, 32, 96, 512], dt, 48,
+                                        [6.0, 3.0, 12.0, 2.0, 1.5], name="opt_mixed"),
+    "zipf_long_runs": lambda dt: wl.custom([5000, 40, 20000], [64, 256, 12], dt, 700, [25.0, 6.0, 9.0],
+                                           index_dist="zipf", zipf_s=1.1, name="opt_zipf"),
+}
+
+
+@pytest.mark.parametrize("optimizer", [tbe.TBE_OPT_ADAGRAD, tbe.TBE_OPT_ADAM])
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("case", sorted(SPECS))
+def test_optimizer_parity(gpu_device, optimizer, dtype, case):
+    print(f"optimizer {optimizer} dtype {dtype} case {case}", flush=True)
+    _run(SPECS[case](dtype), optimizer, tbe.TBE_DTYPE_FP32, gpu_device)
+
+
+@pytest.mark.parametrize("grad_dtype", [tbe.TBE_DTYPE_FP16, tbe.TBE_DTYPE_BF16])
+@pytest.mark.parametrize("optimizer", [tbe.TBE_OPT_ADAGRAD, tbe.TBE_OPT_ADAM])
+def test_optimizer_parity_with_16bit_gradients(gpu_device, optimizer, grad_dtype):
+    print(f"optimizer {optimizer} grad dtype {grad_dtype}", flush=True)
+    _run(SPECS["zipf_long_runs"](1), optimizer, grad_dtype, gpu_device, seed=3)
+
+
+@pytest.mark.parametrize("grad_dtype", [tbe.TBE_DTYPE_FP16, tbe.TBE_DTYPE_BF16])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_rowwise_adagrad_with_16bit_gradients(gpu_device, dtype, grad_dtype):
+    """The same step as the fp32-gradient parity tests, with the gradient stored in 16 bits: the oracle gets
+    the float32 values of exactly those 16-bit numbers."""
+    spec = SPECS["zipf_long_runs"](dtype)
+    dev = gpu_device
+    b = wl.make_batch(spec, "cpu", seed=5)
+    idx, off = b.indices.numpy(), b.offsets.numpy()
+    N, B = b.num_indices, spec.batch
+    w0 = wl.make_weights(spec, "cpu", seed=6).numpy()
+    m0 = np.zeros(spec.total_rows, np.float32)
+    g_t = _round_grad(wl.make_grad(spec, "cpu", seed=7).numpy(), grad_dtype)
+    ref = tl.oracle_step(spec, idx, off, w0, m0, g_t.to(torch.float32).numpy(), 0.01, 1e-8)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, N, device=dev,
+                                       weights=torch.from_numpy(w0.copy()).to(dev), grad_dtype=grad_dtype)
+    op.backward_rowwise_adagrad(torch.from_numpy(idx).to(dev), torch.from_numpy(off).to(dev), B, g_t.to(dev), 0.01,
+                                1e-8, num_indices=N)
+    tl.assert_artifacts_equal(op.artifacts(), ref["art"], "16-bit grad")
+    tl.assert_update_close(spec, ref, w0, m0, op.weights.cpu().numpy(), op.state.cpu().numpy(), 0.01, 1e-8,
+                           "16-bit grad")
+    op.close()
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("case", sorted(SPECS))
+def test_forward_float16_output(gpu_device, dtype, case):
+    spec = SPECS[case](dtype)
+    dev = gpu_device
+    b = wl.make_batch(spec, "cpu", seed=9)
+    idx, off = b.indices.numpy(), b.offsets.numpy()
+    N, B = b.num_indices, spec.batch
+    w0 = wl.make_weights(spec, "cpu", seed=10).numpy()
+    if case == "mixed_small":
+        w0 = (w0.astype(np.float32) * 300).astype(w0.dtype)     # sums of order 10: well inside fp16's normal range
+    ref, absref = orc.forward(spec.rows, spec.dims, spec.dtype, w0, idx, off, B, want_absref=True)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, N, device=dev,
+                                       weights=torch.from_numpy(w0.copy()).to(dev), output_dtype=tbe.TBE_DTYPE_FP16)
+    out = op.forward(torch.from_numpy(idx).to(dev), torch.from_numpy(off).to(dev), B, num_indices=N)
+    assert out.dtype == torch.float16
+    got = out.float().cpu().numpy().astype(np.float64)
+    r = ref.astype(np.float64)
+    tol = tl.RTOL_FP32 * np.maximum(np.abs(r), absref) + 2.0 ** -11 * np.abs(r) + 2.0 ** -25
+    assert (np.abs(got - r) <= tol).all(), f"max excess {np.max(np.abs(got - r) - tol):.3e}"
+    op.close()
+
+
+def test_wrong_optimizer_entry_point_is_rejected(gpu_device):
+    spec = SPECS["mixed_small"](0)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, 0, spec.batch, 100, device=gpu_device,
+                                       optimizer=tbe.TBE_OPT_ADAM)
+    z = torch.zeros(1, dtype=torch.int64, device=gpu_device)
+    g = torch.zeros(spec.batch, spec.sumD, device=gpu_device)
+    assert tbe.tbe_backward_rowwise_adagrad(op.h, z.int(), z, 0, 0, g, 0.1, 1e-8) == tbe.TBE_ERR_INVALID_ARG
+    assert tbe.tbe_backward_adagrad(op.h, z.int(), z, 0, 0, g, 0.1, 1e-8) == tbe.TBE_ERR_INVALID_ARG
+    assert tbe.tbe_backward_adam(op.h, z.int(), z, 0, 0, g, 0.1, 0.9, 0.999, 1e-8, 0) == tbe.TBE_ERR_INVALID_ARG
+    assert tbe.tbe_backward_adam(op.h, z.int(), z, 0, 0, g, 0.1, 1.0, 0.999, 1e-8, 1) == tbe.TBE_ERR_INVALID_ARG
+    assert tbe.tbe_backward_adam(op.h, z.int(), z, 0, 0, g, 0.1, 0.9, 0.999, 1e-8, 1) == tbe.TBE_OK
+    op.close()

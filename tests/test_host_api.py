@@ -129,3 +129,27 @@ def test_input_side_entry_points_validate_on_the_host():
     assert L.tbe_bucketize_rowwise(1, 4, 2, fake, fake, fake, 1, fake, fake, fake, fake, 8, None) == bad
     assert L.tbe_bucketize_rowwise(1, 4, 1025, fake, fake, fake, 1, fake, fake, fake, fake, 2 ** 40,
                                    None) == tbe.TBE_ERR_UNSUPPORTED
+
+
+def test_optimizer_and_dtype_configuration():
+    rows, dims = [10, 3], [8, 4]
+    elems = 10 * 8 + 3 * 4
+    for opt, want in ((tbe.TBE_OPT_ROWWISE_ADAGRAD, 4 * 13), (tbe.TBE_OPT_ADAGRAD, 4 * elems),
+                      (tbe.TBE_OPT_ADAM, 8 * elems)):
+        rc, h = tbe.tbe_create(rows, dims, 1, 4, 100, optimizer=opt, output_dtype=tbe.TBE_DTYPE_FP16,
+                               grad_dtype=tbe.TBE_DTYPE_BF16)
+        assert rc == tbe.TBE_OK
+        assert tbe.tbe_query_sizes(h, 2)[1]["state_bytes"] == want
+        tbe.tbe_destroy(h)
+    bad = tbe.TBE_ERR_UNSUPPORTED
+    assert tbe.tbe_create(rows, dims, 0, 4, 100, optimizer=3)[0] == bad
+    assert tbe.tbe_create(rows, dims, 0, 4, 100, output_dtype=tbe.TBE_DTYPE_BF16)[0] == bad
+    assert tbe.tbe_create(rows, dims, 0, 4, 100, grad_dtype=3)[0] == bad
+    assert tbe.tbe_create(rows, dims, tbe.TBE_DTYPE_BF16, 4, 100)[0] == bad
+    assert tbe.tbe_create(rows, dims, 0, 4, 100, reserved=1)[0] == bad
+    # entry points of another optimizer are refused before anything is enqueued (unbound handle: NOT_BOUND first)
+    rc, h = tbe.tbe_create(rows, dims, 0, 4, 100, optimizer=tbe.TBE_OPT_ADAM)
+    L = tbe.lib()
+    assert L.tbe_backward_adam(h, None, None, 0, 0, None, 0.1, 0.9, 0.999, 1e-8, 1, None) == tbe.TBE_ERR_NOT_BOUND
+    assert L.tbe_backward_update_adagrad(h, None, 0.1, 1e-8, None) == tbe.TBE_ERR_NOT_BOUND
+    tbe.tbe_destroy(h)
