@@ -46,6 +46,11 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for HBM counter scaling)")
     ap.add_argument("--fwd-only", action="store_true")
+    ap.add_argument("--optimizer", choices=["rowwise_adagrad", "adagrad", "adam"], default="rowwise_adagrad")
+    ap.add_argument("--out-dtype", choices=["fp32", "fp16"], default="fp32",
+                    help="type of the pooled output (Section 8.4 ships it through an FP16 all-to-all)")
+    ap.add_argument("--grad-dtype", choices=["fp32", "fp16", "bf16"], default="fp32",
+                    help="type of the upstream gradient (Section 8.4 receives it through a BF16 all-to-all)")
     ap.add_argument("--inputs", action="store_true",
                     help="time the input-side kernels (row-wise bucketize, (W,T,B)->(T,W,B) permute, lengths->offsets) "
                          "on the chosen config's batch instead of the embedding step")
@@ -66,20 +71,23 @@ def per_table_counts(spec, batch):
 LONG_RUN = 512    # runs longer than this are cut at 128-position chunk borders by the library (kLongRun)
 
 
-def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t):
+def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0):
     """Bytes one launch of each kernel must move, two ways.
     compulsory: every distinct byte once -- what an ideal cache would leave for HBM; the roofline numerator.
     logical:    every lookup counted as a row read -- a throughput figure that caches can push past the HBM peak.
-    n_t / u_t: lookups / distinct rows per table; nlong_t / ulong_t: lookups in / number of runs longer than LONG_RUN."""
+    n_t / u_t: lookups / distinct rows per table; nlong_t / ulong_t: lookups in / number of runs longer than LONG_RUN;
+    so / sg: bytes per output / gradient element; state_per_elem: float32 optimizer states per weight element
+    (0 = one moment per row)."""
     sw = 4 if spec.dtype == 0 else 2
     D = spec.dims.astype(np.float64)
     B = float(spec.batch)
     N = float(n_t.sum())
     U = float(u_t.sum())
     bags = float(spec.T) * B
-    io_fwd = N * 4 + bags * 8 + (B * 4 * D).sum()
-    rmw = (u_t * (2 * D * sw + 8)).sum()
-    slab = B * 4 * D
+    io_fwd = N * 4 + bags * 8 + (B * so * D).sum()
+    state_rw = 8 * D * state_per_elem if state_per_elem else 8.0
+    rmw = (u_t * (2 * D * sw + state_rw)).sum()
+    slab = B * sg * D
     partial_rows = nlong_t / 128.0 + 2 * ulong_t    # one fp32 partial row per chunk a long run touches
     comp = {
         "forward": float((u_t * D * sw).sum() + io_fwd),
@@ -88,13 +96,13 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t):
         "radix_scatter": N * 16,
         "radix_scan": 0.0,
         "runlength": N * 4 + U * 8,
-        "reduce_update": float(N * 4 + U * 8 + np.minimum(n_t * 4 * D, slab).sum() + rmw +
+        "reduce_update": float(N * 4 + U * 8 + np.minimum(n_t * sg * D, slab).sum() + rmw +
                                (partial_rows * 4 * D).sum()),
-        "long_fixup": float((partial_rows * 4 * D + ulong_t * (2 * D * sw + 8)).sum()),
+        "long_fixup": float((partial_rows * 4 * D + ulong_t * (2 * D * sw + state_rw)).sum()),
     }
     logical = dict(comp)
     logical["forward"] = float((n_t * D * sw).sum() + io_fwd)
-    logical["reduce_update"] = float(N * 4 + U * 8 + (n_t * 4 * D).sum() + rmw + (partial_rows * 4 * D).sum())
+    logical["reduce_update"] = float(N * 4 + U * 8 + (n_t * sg * D).sum() + rmw + (partial_rows * 4 * D).sum())
     return comp, logical
 
 
@@ -128,7 +136,7 @@ def cpu_baseline(spec, batch, weights, grad, target_lookups):
         idx_parts.append(batch.indices[lo:hi].cpu().numpy())
         len_parts.append(np.diff(off[t * B:(t + 1) * B + 1].cpu().numpy()))
         w_parts.append(weights[int(woffs[t]):int(woffs[t + 1])].cpu().numpy())
-        g_parts.append(grad[:, int(cols[t]):int(cols[t + 1])].cpu().numpy())
+        g_parts.append(grad[:, int(cols[t]):int(cols[t + 1])].float().cpu().numpy())
     rows = spec.rows[take]
     dims = spec.dims[take]
     indices = np.concatenate(idx_parts).astype(np.int32)
@@ -235,11 +243,28 @@ def main():
     t_setup = time.perf_counter()
     weights = wl.make_weights(spec, dev)
     batches = [wl.make_batch(spec, dev, it=i) for i in range(max(1, args.rotation))]
-    grad = wl.make_grad(spec, dev)
+    opt_id = {"rowwise_adagrad": tbe.TBE_OPT_ROWWISE_ADAGRAD, "adagrad": tbe.TBE_OPT_ADAGRAD,
+              "adam": tbe.TBE_OPT_ADAM}[args.optimizer]
+    dt_id = {"fp32": tbe.TBE_DTYPE_FP32, "fp16": tbe.TBE_DTYPE_FP16, "bf16": tbe.TBE_DTYPE_BF16}
     nmax = max(b.num_indices for b in batches)
     op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, spec.batch, nmax, device=dev,
-                                       weights=weights)
-    out = torch.empty(spec.batch, spec.sumD, dtype=torch.float32, device=dev)
+                                       weights=weights, optimizer=opt_id, output_dtype=dt_id[args.out_dtype],
+                                       grad_dtype=dt_id[args.grad_dtype])
+    grad = wl.make_grad(spec, dev)
+    if args.grad_dtype != "fp32":
+        grad = grad.to(op.grad_torch_dtype)
+    out = torch.empty(spec.batch, spec.sumD, dtype=op.out_torch_dtype, device=dev)
+
+    def backward(b):
+        if opt_id == tbe.TBE_OPT_ROWWISE_ADAGRAD:
+            op.backward_rowwise_adagrad(b.indices, b.offsets, spec.batch, grad, spec.lr, spec.eps,
+                                        num_indices=b.num_indices)
+        elif opt_id == tbe.TBE_OPT_ADAGRAD:
+            op.backward_adagrad(b.indices, b.offsets, spec.batch, grad, spec.lr, spec.eps, num_indices=b.num_indices)
+        else:
+            op.backward_adam(b.indices, b.offsets, spec.batch, grad, spec.lr, 0.9, 0.999, spec.eps, 1,
+                             num_indices=b.num_indices)
+
     flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if args.flush else None
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
@@ -262,8 +287,7 @@ def main():
             return
         op.forward(b.indices, b.offsets, spec.batch, out=out, num_indices=b.num_indices)
         if not args.fwd_only:
-            op.backward_rowwise_adagrad(b.indices, b.offsets, spec.batch, grad, spec.lr, spec.eps,
-                                        num_indices=b.num_indices)
+            backward(b)
 
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -308,7 +332,8 @@ def main():
         is_long = lens > LONG_RUN
         nlong_t = torch.bincount(tab[is_long], weights=lens[is_long].double(), minlength=spec.T).cpu().numpy()
         ulong_t = torch.bincount(tab[is_long], minlength=spec.T).cpu().numpy().astype(np.float64)
-    comp, logical = kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t)
+    comp, logical = kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=out.element_size(), sg=grad.element_size(),
+                                 state_per_elem={0: 0, 1: 1, 2: 2}[opt_id])
 
     kernels = {}
     for name, (launches, ms) in prof.items():
@@ -340,7 +365,7 @@ def main():
     fwd_ms = kernels.get("forward", {}).get("ms_per_step", 0.0)
     bwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k != "forward")
     result = {
-        "metric": "tbe_fwd_bwd_rowwise_adagrad_lookups_per_s" if not args.fwd_only else "tbe_fwd_lookups_per_s",
+        "metric": (f"tbe_fwd_bwd_{args.optimizer}_lookups_per_s") if not args.fwd_only else "tbe_fwd_lookups_per_s",
         "value": lookups / elapsed,
         "unit": "lookups/s",
         "n_gpus": 1,
@@ -357,6 +382,9 @@ def main():
             "tables": spec.T,
             "batch": spec.batch,
             "storage": "fp32" if spec.dtype == 0 else "fp16",
+            "optimizer": args.optimizer,
+            "output_dtype": args.out_dtype,
+            "grad_dtype": args.grad_dtype,
             "lookups_per_step": lookups / args.steps,
             "unique_rows_last_step": num_unique,
             "table_bytes": spec.weight_bytes,
@@ -372,7 +400,7 @@ def main():
         "step_compulsory_GBps": round(sum(comp.values()) / (ms_per_step * 1e-3) / 1e9, 1) if not args.fwd_only else None,
         "setup_s": round(setup_s, 2),
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and opt_id == tbe.TBE_OPT_ROWWISE_ADAGRAD:
         result["cpu_baseline"] = cpu_baseline(spec, last, weights, grad, args.cpu_sample_lookups)
     else:
         result["cpu_baseline"] = None
