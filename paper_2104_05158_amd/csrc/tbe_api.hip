@@ -174,7 +174,7 @@ void plan_workspace(tbe_s* h)
     h->max_tiles = ceil_div(nmax, kSortTile) + h->T;
     h->off_tile_base = take(4 * (size_t)(h->T + 1));
     h->off_tstart = take(4 * (size_t)(h->T + 1));
-    h->off_tile_table = take(4 * (size_t)h->max_tiles);
+    h->off_tile_table = take(sizeof(TileDesc) * (size_t)h->max_tiles);
     const int64_t hist_len = 256 * h->max_tiles;
     h->off_hist = take(4 * (size_t)hist_len);
     const int64_t rl_tiles = std::max<int64_t>(1, ceil_div(nmax, kRlTile));
@@ -474,7 +474,7 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
     SortPlan pl;
     pl.tile_base = h->ws<int32_t>(h->off_tile_base);
     pl.tstart = h->ws<int32_t>(h->off_tstart);
-    pl.tile_table = h->ws<int32_t>(h->off_tile_table);
+    pl.tiles = h->ws<TileDesc>(h->off_tile_table);
     // upper bound of the number of tiles for THIS call (the exact number is only known on the device)
     const int max_tiles = (int)std::min<int64_t>(h->max_tiles, ceil_div(n, kSortTile) + h->T);
     {   // a2: table borders -> tile plan (keys are the caller's indices; payloads are made in the first pass)
@@ -482,7 +482,7 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
         hipLaunchKernelGGL(sort_plan_tables_kernel, dim3(1), dim3(256), 0, st, d_offsets, batch, h->T,
                            h->ws<int32_t>(h->off_tile_base), h->ws<int32_t>(h->off_tstart), counters);
         hipLaunchKernelGGL(sort_plan_tiles_kernel, dim3((unsigned)ceil_div(max_tiles, 256)), dim3(256), 0, st,
-                           pl.tile_base, h->T, h->ws<int32_t>(h->off_tile_table), max_tiles);
+                           pl.tile_base, pl.tstart, h->T, h->ws<TileDesc>(h->off_tile_table), max_tiles);
         TBE_LAUNCH_CHECK(h, "sort_plan kernels");
     }
 

@@ -307,10 +307,20 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
 // a tile is (wavefront, round, lane) = ascending position, so equal digits keep their input order
 // and the whole sort is stable.
 
+struct TileDesc {        // 32 bytes: everything a workgroup needs to know about its tile, in one load
+    int32_t t;           // table, -1 past the last tile
+    int32_t first;       // first position of the tile
+    int32_t cnt;         // positions in the tile (1..kSortTile)
+    int32_t hstride;     // tiles of the table = distance between consecutive digits in the histogram
+    int32_t tbase;       // first tile of the table
+    int32_t local;       // index of the tile inside its table
+    int32_t pad[2];
+};
+
 struct SortPlan {
     const int32_t* tile_base;    // [T+1] first tile of table t; [T] = number of tiles
     const int32_t* tstart;       // [T+1] first position of table t; [T] = n
-    const int32_t* tile_table;   // [max_tiles] table of tile g, -1 past the last tile
+    const TileDesc* tiles;       // [max_tiles]
 };
 
 // one workgroup: table borders -> tile_base / tstart; also clears the per-call counters
@@ -347,13 +357,15 @@ __global__ __launch_bounds__(256) void sort_plan_tables_kernel(const int64_t* __
     }
 }
 
-__global__ __launch_bounds__(256) void sort_plan_tiles_kernel(const int32_t* __restrict__ tile_base, int32_t T,
-                                                              int32_t* __restrict__ tile_table, int32_t max_tiles)
+__global__ __launch_bounds__(256) void sort_plan_tiles_kernel(const int32_t* __restrict__ tile_base,
+                                                              const int32_t* __restrict__ tstart, int32_t T,
+                                                              TileDesc* __restrict__ tiles, int32_t max_tiles)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
     if (g >= max_tiles)
         return;
-    int t = -1;
+    TileDesc d;
+    d.t = -1; d.first = 0; d.cnt = 0; d.hstride = 0; d.tbase = 0; d.local = 0; d.pad[0] = d.pad[1] = 0;
     if (g < tile_base[T]) {
         int a = 0, c = T;  // last a in [0, T) with tile_base[a] <= g
         while (c - a > 1) {
@@ -363,9 +375,15 @@ __global__ __launch_bounds__(256) void sort_plan_tiles_kernel(const int32_t* __r
             else
                 c = mid;
         }
-        t = a;
+        const int tb = tile_base[a];
+        d.t = a;
+        d.tbase = tb;
+        d.local = g - tb;
+        d.first = tstart[a] + d.local * kSortTile;
+        d.cnt = min(kSortTile, tstart[a + 1] - d.first);
+        d.hstride = tile_base[a + 1] - tb;
     }
-    tile_table[g] = t;
+    tiles[g] = d;
 }
 
 struct TileGeom {
@@ -378,17 +396,15 @@ struct TileGeom {
 
 __device__ __forceinline__ bool tile_geom(const SortPlan& pl, int g, int nd, TileGeom& tg)
 {
-    const int t = pl.tile_table[g];
-    if (t < 0)
+    const int4 a = *reinterpret_cast<const int4*>(&pl.tiles[g]);            // t, first, cnt, hstride
+    const int2 b = *reinterpret_cast<const int2*>(&pl.tiles[g].tbase);      // tbase, local
+    if (a.x < 0)
         return false;
-    const int tb = pl.tile_base[t];
-    const int lo = pl.tstart[t];
-    const int l = g - tb;
-    tg.t = t;
-    tg.first = lo + l * kSortTile;
-    tg.cnt = min(kSortTile, pl.tstart[t + 1] - tg.first);
-    tg.hstride = pl.tile_base[t + 1] - tb;
-    tg.hbase = (int64_t)tb * nd + l;
+    tg.t = a.x;
+    tg.first = a.y;
+    tg.cnt = a.z;
+    tg.hstride = a.w;
+    tg.hbase = (int64_t)b.x * nd + b.y;
     return true;
 }
 
@@ -406,7 +422,7 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t dg, bool valid, int bit
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     SortPlan pl, const uint32_t* __restrict__ keys, uint32_t* __restrict__ hist, int shift, int bits)
 {
-    __shared__ uint32_t s_hist[kSortThreads / kWave][256];
+    __shared__ uint32_t s_hist[256];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int nd = 1 << bits;
@@ -414,35 +430,37 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     TileGeom tg;
     if (!tile_geom(pl, blockIdx.x, nd, tg))
         return;
-    for (int i = threadIdx.x; i < (kSortThreads / kWave) * 256; i += kSortThreads)
-        (&s_hist[0][0])[i] = 0;
-    __syncthreads();
-    volatile uint32_t* wh = s_hist[wave];
     const int base = tg.first + wave * (kSortTile / (kSortThreads / kWave));
     const int end = tg.first + tg.cnt;
-    const uint64_t lt = (1ull << lane) - 1ull;
     // all 16 key loads are issued before the first one is used (positions past the tile are clamped)
     uint32_t key[kSortKeysPerThread];
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r)
         key[r] = keys[min(base + r * kWave + lane, end - 1)];
+    if ((int)threadIdx.x < nd)
+        s_hist[threadIdx.x] = 0;
+    __syncthreads();
+    // Counting needs no ranks: when the 64 keys of a round share one digit (identical rows are adjacent
+    // from the second pass on) one lane adds the whole count, otherwise every lane adds 1; LDS integer
+    // atomics, so the totals do not depend on the order.
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
         const int q = base + r * kWave + lane;
-        const bool valid = q < end;
+        const bool valid = q < end;                   // valid lanes are a prefix of the wavefront
         const uint32_t dg = (key[r] >> shift) & mask;
-        const uint64_t peers = match_digit(dg, valid, bits);
-        if (valid && (peers & lt) == 0)
-            wh[dg] = wh[dg] + (uint32_t)__popcll(peers);
+        const uint64_t vm = __ballot(valid);
+        const uint32_t d0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)dg);
+        const uint64_t same = __ballot(dg == d0);
+        if ((same & vm) == vm) {
+            if (lane == 0 && vm != 0ull)
+                atomicAdd(&s_hist[d0], (uint32_t)__popcll(vm));
+        } else if (valid) {
+            atomicAdd(&s_hist[dg], 1u);
+        }
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < nd; d += kSortThreads) {
-        uint32_t s = 0;
-#pragma unroll
-        for (int w = 0; w < kSortThreads / kWave; ++w)
-            s += s_hist[w][d];
-        hist[tg.hbase + (int64_t)d * tg.hstride] = s;
-    }
+    if ((int)threadIdx.x < nd)
+        hist[tg.hbase + (int64_t)threadIdx.x * tg.hstride] = s_hist[threadIdx.x];
 }
 
 // FIRST: keys_in is the caller's index array and the payload is computed from the offsets;
