@@ -482,7 +482,8 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
         hipLaunchKernelGGL(sort_plan_tables_kernel, dim3(1), dim3(256), 0, st, d_offsets, batch, h->T,
                            h->ws<int32_t>(h->off_tile_base), h->ws<int32_t>(h->off_tstart), counters);
         hipLaunchKernelGGL(sort_plan_tiles_kernel, dim3((unsigned)ceil_div(max_tiles, 256)), dim3(256), 0, st,
-                           pl.tile_base, pl.tstart, h->T, h->ws<TileDesc>(h->off_tile_table), max_tiles);
+                           pl.tile_base, pl.tstart, d_offsets, batch, h->T, h->ws<TileDesc>(h->off_tile_table),
+                           max_tiles);
         TBE_LAUNCH_CHECK(h, "sort_plan kernels");
     }
 

@@ -314,7 +314,8 @@ struct TileDesc {        // 32 bytes: everything a workgroup needs to know about
     int32_t hstride;     // tiles of the table = distance between consecutive digits in the histogram
     int32_t tbase;       // first tile of the table
     int32_t local;       // index of the tile inside its table
-    int32_t pad[2];
+    int32_t bag_lo;      // bag (inside the table's batch) of the tile's first position ...
+    int32_t bag_hi;      // ... and of its last one
 };
 
 struct SortPlan {
@@ -357,15 +358,31 @@ __global__ __launch_bounds__(256) void sort_plan_tables_kernel(const int64_t* __
     }
 }
 
+// last bag b in [0, B) of table t with offsets[t*B + b] <= q
+__device__ __forceinline__ int bag_of_position(const int64_t* __restrict__ offsets, int64_t j0, int B, int64_t q)
+{
+    int a = 0, c = B;
+    while (c - a > 1) {
+        const int mid = (a + c) >> 1;
+        if (offsets[j0 + mid] <= q)
+            a = mid;
+        else
+            c = mid;
+    }
+    return a;
+}
+
 __global__ __launch_bounds__(256) void sort_plan_tiles_kernel(const int32_t* __restrict__ tile_base,
-                                                              const int32_t* __restrict__ tstart, int32_t T,
-                                                              TileDesc* __restrict__ tiles, int32_t max_tiles)
+                                                              const int32_t* __restrict__ tstart,
+                                                              const int64_t* __restrict__ offsets, int32_t B,
+                                                              int32_t T, TileDesc* __restrict__ tiles,
+                                                              int32_t max_tiles)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
     if (g >= max_tiles)
         return;
     TileDesc d;
-    d.t = -1; d.first = 0; d.cnt = 0; d.hstride = 0; d.tbase = 0; d.local = 0; d.pad[0] = d.pad[1] = 0;
+    d.t = -1; d.first = 0; d.cnt = 0; d.hstride = 0; d.tbase = 0; d.local = 0; d.bag_lo = d.bag_hi = 0;
     if (g < tile_base[T]) {
         int a = 0, c = T;  // last a in [0, T) with tile_base[a] <= g
         while (c - a > 1) {
@@ -382,6 +399,8 @@ __global__ __launch_bounds__(256) void sort_plan_tiles_kernel(const int32_t* __r
         d.first = tstart[a] + d.local * kSortTile;
         d.cnt = min(kSortTile, tstart[a + 1] - d.first);
         d.hstride = tile_base[a + 1] - tb;
+        d.bag_lo = bag_of_position(offsets, (int64_t)a * B, B, d.first);
+        d.bag_hi = bag_of_position(offsets, (int64_t)a * B, B, d.first + d.cnt - 1);
     }
     tiles[g] = d;
 }
@@ -478,7 +497,6 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     __shared__ uint32_t s_whist[kWaves][256];
     __shared__ uint32_t s_dstart[256];
     __shared__ uint32_t s_goff[256];
-    __shared__ int32_t s_bag[2];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
@@ -492,20 +510,6 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 
     for (int i = threadIdx.x; i < kWaves * 256; i += kSortThreads)
         (&s_whist[0][0])[i] = 0;
-    if (FIRST && threadIdx.x < 2) {
-        // bag (inside table t) of the tile's first / last position: last j with offsets[j] <= q
-        const int64_t q = threadIdx.x == 0 ? tg.first : end - 1;
-        const int64_t j0 = (int64_t)tg.t * B;
-        int a = 0, c = B;
-        while (c - a > 1) {
-            const int mid = (a + c) >> 1;
-            if (offsets[j0 + mid] <= q)
-                a = mid;
-            else
-                c = mid;
-        }
-        s_bag[threadIdx.x] = a;
-    }
     __syncthreads();
 
     uint32_t key[kSortKeysPerThread];
@@ -522,7 +526,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     if (FIRST) {
         // payload = bag of the position: the borders of the bags the tile touches are staged in
         // LDS (in the space the reordered payloads use later) and searched there
-        const int b_lo = s_bag[0], b_hi = s_bag[1];
+        const int2 bags = *reinterpret_cast<const int2*>(&pl.tiles[blockIdx.x].bag_lo);
+        const int b_lo = bags.x, b_hi = bags.y;
         const int nb = b_hi - b_lo + 1;
         const int64_t j0 = (int64_t)tg.t * B + b_lo;
         if (nb <= kSortTile) {
