@@ -69,11 +69,48 @@ def test_several_sort_tiles_and_ragged_tail(gpu_device, dtype):
 
 @pytest.mark.parametrize("total_rows", [2, 255, 257, 70_000, 20_000_000])
 def test_key_bit_budgets(gpu_device, total_rows):
-    # 1, 8, 9, 17 and 25 significant key bits: 1 to 4 radix passes with uneven digit widths
+    # the sort runs over the row-index bits of the tallest table: 1, 7, 8, 16 and 24 bits here, i.e.
+    # 1 to 3 radix passes with even and uneven digit widths
     rows = [total_rows - total_rows // 2, total_rows // 2] if total_rows > 2 else [1, 1]
     spec = wl.custom(rows, [8, 4], 0, 97, 9.0, name=f"bits{total_rows}")
     idx, off, w, g = _np_case(spec, 13)
     tl.full_parity_step(spec, idx, off, w, g, gpu_device, what=f"bits{total_rows}")
+
+
+def test_widest_key_needs_four_passes(gpu_device):
+    # 2^24 + 1 rows in one table: 25 row-index bits -> 4 passes (7,6,6,6); a 1-row table beside it
+    spec = wl.custom([(1 << 24) + 1, 1], [4, 4], 0, 64, [40.0, 3.0], name="bits25")
+    idx, off, w, g = _np_case(spec, 14)
+    idx[:5] = [(1 << 24), 0, (1 << 24), 1 << 23, (1 << 24) - 1]     # the extreme rows occur, one of them twice
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="bits25")
+
+
+def test_segmented_sort_tables_without_lookups(gpu_device):
+    # tables 0, 2 and 4 receive no lookup at all: they own no sort tile and their rows stay untouched
+    spec = wl.custom([50, 3000, 7, 120, 9000], [8, 16, 4, 32, 8], 0, 300, [0.0, 40.0, 0.0, 12.0, 0.0],
+                     pooling_kind="poisson", name="holes")
+    idx, off, w, g = _np_case(spec, 15)
+    assert int(off[300]) == 0 and int(off[900]) == int(off[600]) and int(off[-1]) == int(off[1200]) > 8192
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="holes")
+
+
+def test_first_pass_tile_spanning_more_bags_than_it_has_positions(gpu_device):
+    # mean pooling 0.3: one 8192-position sort tile spans ~27k bags, more than the bag borders the first pass can
+    # stage on chip, so payloads are found by bisection in global memory
+    spec = wl.custom([5000, 800], [8, 4], 0, 60000, [0.3, 0.25], name="sparse_bags")
+    idx, off, w, g = _np_case(spec, 16)
+    assert int(off[60000]) > 2 * 8192
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="sparse_bags")
+
+
+def test_many_small_tables(gpu_device):
+    # 700 tables (more than one block of the table scan), most with a single partly filled sort tile
+    rng = np.random.default_rng(17)
+    rows = rng.integers(3, 400, 700)
+    dims = rng.choice([4, 8, 16], 700)
+    spec = wl.custom(rows, dims, 1, 24, rng.uniform(0.0, 6.0, 700), name="many_tables")
+    idx, off, w, g = _np_case(spec, 18)
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="many_tables")
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
