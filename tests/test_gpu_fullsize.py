@@ -51,10 +51,13 @@ def _sample_tables(spec, rng, extra=3):
     return sorted(pick)
 
 
-@pytest.mark.parametrize("k", [1, 2, 3, 4])
-def test_full_size_config(gpu_device, k):
+@pytest.mark.parametrize("k,variant", [(1, "fp32"), (2, "fp32"), (3, "fp32"), (4, "fp32"), (2, "16bit"), (4, "16bit")])
+def test_full_size_config(gpu_device, k, variant):
+    """variant "16bit": float16 pooled output and bfloat16 upstream gradient (the oracle is fed the float32
+    values of exactly those bfloat16 numbers; the output tolerance gains one fp16 rounding)."""
     dev = gpu_device
     spec = wl.config(k)
+    sixteen = variant == "16bit"
     gc.collect()
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info(dev)
@@ -66,9 +69,13 @@ def test_full_size_config(gpu_device, k):
     weights = wl.make_weights(spec, dev)
     batch = wl.make_batch(spec, dev, it=0)
     grad = wl.make_grad(spec, dev)
+    if sixteen:
+        grad = grad.to(torch.bfloat16)
     N, B, T = batch.num_indices, spec.batch, spec.T
     print(f"[cfg{k}] N={N} T={T} B={B}", flush=True)
-    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, N, device=dev, weights=weights)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, N, device=dev, weights=weights,
+                                       output_dtype=tbe.TBE_DTYPE_FP16 if sixteen else tbe.TBE_DTYPE_FP32,
+                                       grad_dtype=tbe.TBE_DTYPE_BF16 if sixteen else tbe.TBE_DTYPE_FP32)
     assert op.check_inputs(batch.indices, batch.offsets, B, num_indices=N) == tbe.TBE_OK
 
     R = np.concatenate([[0], np.cumsum(spec.rows)])
@@ -99,8 +106,14 @@ def test_full_size_config(gpu_device, k):
         sub_off[1:] = np.cumsum([len(p) for p in pieces])
         ref, absref = orc.forward(np.array([len(need_rows)], np.int64), np.array([D], np.int32), spec.dtype, sub_w,
                                   inv.astype(np.int32), sub_off, len(bags), want_absref=True)
-        got = out[torch.from_numpy(bags).to(dev), int(cols[t]):int(cols[t + 1])].cpu().numpy()
-        worst_f = max(worst_f, tl.assert_forward_close(got, ref, absref, f"cfg{k} table {t}"))
+        got = out[torch.from_numpy(bags).to(dev), int(cols[t]):int(cols[t + 1])].float().cpu().numpy()
+        if sixteen:
+            # one extra rounding of the fp32 sum to fp16 (2^-11 relative, 2^-25 absolute for subnormals)
+            r64 = ref.astype(np.float64)
+            tol = tl.RTOL_FP32 * np.maximum(np.abs(r64), absref) + 2.0 ** -11 * np.abs(r64) + 2.0 ** -25
+            assert (np.abs(got.astype(np.float64) - r64) <= tol).all(), f"cfg{k} table {t} fp16 output"
+        else:
+            worst_f = max(worst_f, tl.assert_forward_close(got, ref, absref, f"cfg{k} table {t}"))
     print(f"[cfg{k}] forward sampled ok, worst rel err {worst_f:.2e}", flush=True)
 
     # ---------------- backward: record what the oracle needs before the in-place update
@@ -170,7 +183,7 @@ def test_full_size_config(gpu_device, k):
         sub_idx = np.searchsorted(rows_s, idx_t[pos]).astype(np.int32)
         sub_off = np.zeros(B + 1, np.int64)
         sub_off[1:] = np.cumsum(np.bincount(bag_of, minlength=B))
-        g_t = np.ascontiguousarray(grad[:, int(cols[t]):int(cols[t + 1])].cpu().numpy())
+        g_t = np.ascontiguousarray(grad[:, int(cols[t]):int(cols[t + 1])].float().cpu().numpy())
         w_ref = s["w_old"].ravel().copy()
         m_ref = np.zeros(len(rows_s), np.float32)
         det = orc.backward_rowwise_adagrad(np.array([len(rows_s)], np.int64), np.array([D], np.int32), spec.dtype,
