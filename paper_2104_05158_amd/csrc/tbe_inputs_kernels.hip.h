@@ -411,7 +411,6 @@ __global__ __launch_bounds__(kThreads) void bucketize_place_kernel(const int64_t
             s_next[d] = offsets_out[((int64_t)d * T + t0) * B + (j0 - t0 * B)];
     }
     const uint64_t lt = (1ull << lane) - 1ull;
-    volatile uint32_t* wh = s_whist[wave];
 
     for (int tile0 = 0; tile0 < total; tile0 += kBuckTile) {
         const int tile_cnt = min(kBuckTile, total - tile0);
@@ -437,10 +436,10 @@ __global__ __launch_bounds__(kThreads) void bucketize_place_kernel(const int64_t
             local[k] = (int32_t)(r[k] - w * blk);
             dig[k] = w;
             const uint64_t peers = match_key(w, valid, wbits);
-            const uint32_t pre = valid ? wh[w] : 0u;
+            const uint32_t pre = s_whist[wave][w];    // indexed as the LDS array it is (no generic pointer)
             const uint32_t below = (uint32_t)__popcll(peers & lt);
             if (valid && below == 0)
-                wh[w] = pre + (uint32_t)__popcll(peers);
+                s_whist[wave][w] = pre + (uint32_t)__popcll(peers);
             rank[k] = pre + below;
         }
         __syncthreads();

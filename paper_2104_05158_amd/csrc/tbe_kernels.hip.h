@@ -565,7 +565,10 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             }
         }
     }
-    volatile uint32_t* wh = s_whist[wave];
+    // The wavefront's private counters are indexed as the LDS array they are (a pointer to the row would be
+    // a generic pointer: flat loads and stores, each waited for).  LDS operations of one wavefront execute
+    // in order and the compiler keeps a load behind a store that may alias it, so a round sees the counts
+    // of the rounds before it.
     const uint64_t lt = (1ull << lane) - 1ull;
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r) {
@@ -573,10 +576,10 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
         const bool valid = q < end;
         const uint32_t dg = (key[r] >> shift) & mask;
         const uint64_t peers = match_digit(dg, valid, bits);
-        const uint32_t pre = valid ? wh[dg] : 0u;
+        const uint32_t pre = s_whist[wave][dg];
         const uint32_t below = (uint32_t)__popcll(peers & lt);
         if (valid && below == 0)
-            wh[dg] = pre + (uint32_t)__popcll(peers);
+            s_whist[wave][dg] = pre + (uint32_t)__popcll(peers);
         rank[r] = pre + below;
     }
     __syncthreads();
