@@ -427,15 +427,28 @@ __device__ __forceinline__ bool tile_geom(const SortPlan& pl, int g, int nd, Til
     return true;
 }
 
+// Lanes of the wavefront whose digit equals this lane's (valid lanes only).  Bit b of every lane is
+// broadcast by a ballot; a lane keeps the lanes whose bit agrees with its own.  The loop is unrolled
+// for the largest digit width with a uniform guard, so no bit position costs a loop iteration.
 __device__ __forceinline__ uint64_t match_digit(uint32_t dg, bool valid, int bits)
 {
-    uint64_t peers = __ballot(valid);
-    for (int b = 0; b < bits; ++b) {
-        const bool bit = (dg >> b) & 1u;
-        const uint64_t bal = __ballot(bit);
-        peers &= bit ? bal : ~bal;
+    uint32_t lo, hi;
+    {
+        const uint64_t v = __ballot(valid);
+        lo = (uint32_t)v;
+        hi = (uint32_t)(v >> 32);
     }
-    return peers;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        if (b < bits) {
+            const uint32_t m = (uint32_t)(((int32_t)(dg << (31 - b))) >> 31);   // all ones if bit b is set
+            const uint64_t bal = __ballot(m != 0u);
+            // lanes whose bit differs from mine drop out: peers &= ~(bal ^ m)
+            lo &= ~((uint32_t)bal ^ m);
+            hi &= ~((uint32_t)(bal >> 32) ^ m);
+        }
+    }
+    return ((uint64_t)hi << 32) | lo;
 }
 
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
