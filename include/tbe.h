@@ -145,8 +145,9 @@ TBE_API tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const
  *   m[t,r]  += (1/D_t) * sum_d G[t,r,d]^2
  *   W_t[r,:] -= lr * G[t,r,:] / (sqrt(m[t,r]) + eps)
  * computed in fp32 and rounded to the storage type (nearest even).  Rows not looked up are not
- * written.  Implementation: (table,row) keys are built, radix-sorted (stable) and run-length
- * segmented in the workspace, then every run is reduced on chip and its row updated once.
+ * written.  Implementation: the lookups are radix-sorted by (table, row) (stable; the sort is
+ * segmented by table and reads the caller's indices directly) and run-length segmented in the
+ * workspace, then every run is reduced on chip and its row updated once.
  * The integer artefacts stay in the workspace until the next backward call (tbe_backward_artifacts).
  * d_grad_out is [batch, sumD] in the configured gradient type.
  * Errors: as tbe_forward; INVALID_ARG if the handle was created for another optimizer.
@@ -178,7 +179,7 @@ TBE_API tbe_status_t tbe_backward_adam(tbe_handle_t h, const int32_t* d_indices,
 /*
  * The same backward pass in two calls, for callers that overlap work (Section 4.2 pipelines
  * independent stages on separate streams).  tbe_backward_sort enqueues the part that needs only the
- * batch's (indices, offsets): key build, radix sort, run-length segmentation (Section 5.1 "gradient
+ * batch's (indices, offsets): sort plan, radix sort, run-length segmentation (Section 5.1 "gradient
  * sorting by rows"); it may run on another stream, concurrently with tbe_forward or with dense
  * layers.  tbe_backward_update_<optimizer> enqueues the aggregation + optimizer step
  * (Sections 5.1, 5.2) for the batch sorted last; the caller must order it after that sort (same

@@ -3,7 +3,7 @@
 //
 // Section 5.1 of arxiv 2104.05158 asks for one forward launch and one fused backward+optimizer
 // step for all tables of a GPU; here the forward is literally one kernel and the backward is a
-// fixed sequence (key build, radix sort passes, run-length, fused reduce+AdaGrad, long-run fix-up)
+// fixed sequence (sort plan, radix sort passes, run-length, fused reduce+optimizer, long-run fix-up)
 // enqueued on the caller's stream without any host synchronisation.
 #include "tbe.h"
 
