@@ -2,7 +2,7 @@
 """Benchmark of the table-batched embedding-bag hot path on one MI355X.
 
 A step = one pass of the whole path over one synthetic batch: tbe_forward, then
-tbe_backward_rowwise_adagrad (key build, radix sort, run-length, fused reduce + row-wise AdaGrad,
+tbe_backward_rowwise_adagrad (sort plan, radix sort, run-length, fused reduce + row-wise AdaGrad,
 long-run fix-up) on the same batch.  Inputs, weights and optimizer state are resident in HBM before
 the timed region; a rotation of pre-generated batches (different seeds) is used so that no step
 re-reads the previous step's index stream.
