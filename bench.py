@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for HBM counter scaling)")
     ap.add_argument("--fwd-only", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each batch's step in a HIP graph and time the replays (the per-kernel figures "
+                         "then come from the same number of eager steps run afterwards)")
     ap.add_argument("--optimizer", choices=["rowwise_adagrad", "adagrad", "adam"], default="rowwise_adagrad")
     ap.add_argument("--out-dtype", choices=["fp32", "fp16"], default="fp32",
                     help="type of the pooled output (Section 8.4 ships it through an FP16 all-to-all)")
@@ -301,15 +304,39 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    op.profile_enable(args.steps + 1)
-    lookups = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-        lookups += batches[(args.warmup + i) % len(batches)].num_indices
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    lookups = sum(batches[(args.warmup + i) % len(batches)].num_indices for i in range(args.steps))
+    if args.graph:
+        # one captured step per batch of the rotation; the library only enqueues kernels, so capture is legal
+        assert not overlap and flush_buf is None, "--graph is timed without --overlap / --flush"
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        graphs = []
+        for j in range(len(batches)):
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph, stream=cap):
+                step(j)
+            graphs.append(gph)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % len(graphs)].replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        op.profile_enable(args.steps + 1)
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+    else:
+        op.profile_enable(args.steps + 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     prof = op.profile_read()
     op.profile_enable(0)
 
@@ -392,6 +419,7 @@ def main():
             "rotation": len(batches),
             "cache_flush": bool(args.flush),
             "streams": 2 if overlap else 1,
+            "hip_graph": bool(args.graph),
         },
         "roofline": roofline,
         "kernels": kernels,

@@ -304,3 +304,47 @@ def test_profile_slots(gpu_device):
     assert prof["forward"][0] == 3 and prof["reduce_update"][0] == 3 and prof["radix_scatter"][0] == 3 * 2
     assert all(ms >= 0 for _, ms in prof.values())
     op.profile_enable(0)
+
+
+def test_step_captured_in_a_hip_graph_replays_like_eager(gpu_device):
+    """forward + backward only enqueue kernels on the caller's stream (no allocation, no memset, no host
+    synchronisation), so a caller can capture a whole step in a HIP graph.  Three replays, with eager work and
+    synchronisations in between, must leave exactly the state that three eager steps leave."""
+    spec = wl.custom([3000, 64, 900], [64, 16, 128], 1, 256, [20.0, 5.0, 9.0], index_dist="zipf", name="graph")
+    idx, off, w, g = _np_case(spec, 41)
+    dev = gpu_device
+    N, B = int(off[-1]), spec.batch
+    d_idx, d_off, d_g = (torch.from_numpy(x).to(dev) for x in (idx, off, g))
+
+    def fresh():
+        return tl.make_op(spec, dev, max_indices=N, weights=torch.from_numpy(w.copy()).to(dev))
+
+    # eager reference: three steps, keeping the output of each forward
+    op_e = fresh()
+    outs_e = []
+    for _ in range(3):
+        outs_e.append(op_e.forward(d_idx, d_off, B, num_indices=N).clone())
+        op_e.backward_rowwise_adagrad(d_idx, d_off, B, d_g, 0.05, 1e-8, num_indices=N)
+    torch.cuda.synchronize()
+
+    op_g = fresh()
+    out_g = torch.empty(B, spec.sumD, dtype=torch.float32, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        op_g.forward(d_idx, d_off, B, out=out_g, num_indices=N)
+        op_g.backward_rowwise_adagrad(d_idx, d_off, B, d_g, 0.05, 1e-8, num_indices=N)
+    torch.cuda.synchronize()
+    # capturing does not execute: the state is still the initial one
+    assert torch.equal(op_g.weights, torch.from_numpy(w).to(dev)) and not op_g.state.any().item()
+    scratch = torch.zeros(1 << 20, device=dev)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, outs_e[k]), f"replay {k}: forward output differs from the eager step"
+        scratch.add_(1.0)                       # unrelated eager work between the replays
+        assert float(scratch.sum().item()) == (k + 1) * scratch.numel()
+    assert torch.equal(op_g.weights, op_e.weights) and torch.equal(op_g.state, op_e.state)
+    op_e.close()
+    op_g.close()
