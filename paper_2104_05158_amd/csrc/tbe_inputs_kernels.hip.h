@@ -353,17 +353,28 @@ __global__ __launch_bounds__(kThreads) void bucketize_count_kernel(const int64_t
         s_cnt[i] = 0;
     const int64_t base = load_bags(sb, rows, offsets, j0, nb, B, W);
     const int total = sb.off[nb];
-    for (int p0 = 0; p0 < total; p0 += kThreads * 4) {
-        uint32_t r[4];
+    // Counting does not depend on the order, so a thread takes kBuckPerThread CONSECUTIVE positions: one bag
+    // search for the first of them, then it only steps over the bag borders it meets.
+    for (int p0 = threadIdx.x * kBuckPerThread; p0 < total; p0 += kThreads * kBuckPerThread) {
+        uint32_t r[kBuckPerThread];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            r[u] = (uint32_t)indices[base + min(p0 + u * kThreads + (int)threadIdx.x, total - 1)];
+        for (int u = 0; u < kBuckPerThread; ++u)
+            r[u] = (uint32_t)indices[base + min(p0 + u, total - 1)];
+        int a = find_bag(sb.off, nb, p0);
+        int next = sb.off[a + 1];
+        uint32_t blk = sb.blk[a];
+        float rcp = sb.rcp[a];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int p = p0 + u * kThreads + threadIdx.x;
+        for (int u = 0; u < kBuckPerThread; ++u) {
+            const int p = p0 + u;
             if (p < total) {
-                const int a = find_bag(sb.off, nb, p);
-                const uint32_t w = min(div_rows(r[u], sb.blk[a], sb.rcp[a]), (uint32_t)(W - 1));  // clamp: invalid rows only
+                while (p >= next && a + 1 < nb) {   // p < total = off[nb]: a stays below nb even for bad offsets
+                    ++a;
+                    next = sb.off[a + 1];
+                    blk = sb.blk[a];
+                    rcp = sb.rcp[a];
+                }
+                const uint32_t w = min(div_rows(r[u], blk, rcp), (uint32_t)(W - 1));  // clamp: invalid rows only
                 atomicAdd(&s_cnt[w * nbags + a], 1);
             }
         }
