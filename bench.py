@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--optimizer", choices=["rowwise_adagrad", "adagrad", "adam"], default="rowwise_adagrad")
     ap.add_argument("--out-dtype", choices=["fp32", "fp16"], default="fp32",
                     help="type of the pooled output (Section 8.4 ships it through an FP16 all-to-all)")
+    ap.add_argument("--layout", choices=["batch", "table"], default="batch",
+                    help="layout of the pooled output and the upstream gradient: [B, sumD] rows, or one [B, D_t] "
+                         "block per table")
     ap.add_argument("--grad-dtype", choices=["fp32", "fp16", "bf16"], default="fp32",
                     help="type of the upstream gradient (Section 8.4 receives it through a BF16 all-to-all)")
     ap.add_argument("--inputs", action="store_true",
@@ -252,7 +255,8 @@ def main():
     nmax = max(b.num_indices for b in batches)
     op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, spec.batch, nmax, device=dev,
                                        weights=weights, optimizer=opt_id, output_dtype=dt_id[args.out_dtype],
-                                       grad_dtype=dt_id[args.grad_dtype])
+                                       grad_dtype=dt_id[args.grad_dtype],
+                                       layout=tbe.TBE_LAYOUT_TABLE_MAJOR if args.layout == "table" else 0)
     grad = wl.make_grad(spec, dev)
     if args.grad_dtype != "fp32":
         grad = grad.to(op.grad_torch_dtype)
@@ -412,6 +416,7 @@ def main():
             "optimizer": args.optimizer,
             "output_dtype": args.out_dtype,
             "grad_dtype": args.grad_dtype,
+            "layout": args.layout,
             "lookups_per_step": lookups / args.steps,
             "unique_rows_last_step": num_unique,
             "table_bytes": spec.weight_bytes,

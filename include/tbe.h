@@ -73,6 +73,12 @@ enum { TBE_POOLING_SUM = 0 };
 /* Sparse optimizer fused into the backward pass.  Section 5.2 describes the row-wise AdaGrad;
  * Section 5.1 names (element-wise) AdaGrad and Adam as further non-linear optimizers it serves. */
 enum { TBE_OPT_ROWWISE_ADAGRAD = 0, TBE_OPT_ADAGRAD = 1, TBE_OPT_ADAM = 2 };
+/* Layout of d_out and d_grad_out.  BATCH_MAJOR: one row of sumD values per sample, table t in columns
+ * [c_t, c_t + D_t) -- what a sample's feature interaction consumes.  TABLE_MAJOR: one contiguous
+ * [batch, D_t] block per table, table t's block starting at element batch * c_t -- what a table-wise
+ * all-to-all ships per table, and the friendlier one for the backward pass, whose gradient-row gathers
+ * then stay inside a few MB per table instead of striding over the whole [batch, sumD] array. */
+enum { TBE_LAYOUT_BATCH_MAJOR = 0, TBE_LAYOUT_TABLE_MAJOR = 1 };
 
 typedef struct {
     int32_t num_tables;     /* T >= 1 */
@@ -85,7 +91,7 @@ typedef struct {
     int32_t optimizer;      /* TBE_OPT_*: fixes the size of the state buffer and which backward entry points apply */
     int32_t output_dtype;   /* type of d_out: TBE_DTYPE_FP32, or TBE_DTYPE_FP16 (fp32 sums rounded to nearest even) */
     int32_t grad_dtype;     /* type of d_grad_out: TBE_DTYPE_FP32, TBE_DTYPE_FP16 or TBE_DTYPE_BF16; sums stay fp32 */
-    int32_t reserved;       /* 0 */
+    int32_t layout;         /* TBE_LAYOUT_*: layout of d_out and d_grad_out */
 } tbe_config_t;
 /* The 16-bit output / gradient types follow Section 8.4: the pooled embeddings leave the operator
  * through an FP16 all-to-all and their gradients come back through a BF16 one, so that precision is
@@ -99,7 +105,7 @@ typedef struct {
  * tables that are fused into one operator on this GPU.
  * Errors: INVALID_ARG (null, T < 1, rows/dims not positive, negative sizes),
  *         UNSUPPORTED (dim not a multiple of 4 or > 512, sum of rows >= 2^32 - 1, sizes too large,
- *         unknown dtype/pooling/optimizer, BF16 tables or BF16 output, reserved != 0).
+ *         unknown dtype/pooling/optimizer/layout, BF16 tables or BF16 output).
  */
 TBE_API tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle);
 

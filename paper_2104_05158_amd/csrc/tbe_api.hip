@@ -62,6 +62,7 @@ struct tbe_s {
     int optimizer = 0;
     int out_dtype = 0;
     int grad_dtype = 0;
+    int layout = 0;
     int64_t weight_elems = 0;
     int max_batch = 0;
     int64_t max_indices = 0;
@@ -232,7 +233,7 @@ tbe_status_t launch_forward(tbe_s* h, const int32_t* idx, const int64_t* off, in
     const void* zero = h->ws<void>(h->off_zero);
 #define FWD(EPL, KMAX)                                                                              \
     hipLaunchKernelGGL((forward_kernel<WT, EPL, KMAX, OT>), grid, block, 0, st, meta, w, idx, off, out, \
-                       zero, batch, num_bags, sumD, n_total, bpw)
+                       zero, batch, num_bags, sumD, n_total, bpw, h->layout)
     if constexpr (sizeof(WT) == 4) {
         if (h->fwd_kmax == 1)
             FWD(4, 1);
@@ -280,7 +281,7 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
         if (cfg->rows[t] <= 0 || cfg->dims[t] <= 0)
             return TBE_ERR_INVALID_ARG;
     if ((cfg->weight_dtype != TBE_DTYPE_FP32 && cfg->weight_dtype != TBE_DTYPE_FP16) ||
-        cfg->pooling != TBE_POOLING_SUM || cfg->reserved != 0 ||
+        cfg->pooling != TBE_POOLING_SUM || (cfg->layout != TBE_LAYOUT_BATCH_MAJOR && cfg->layout != TBE_LAYOUT_TABLE_MAJOR) ||
         (cfg->optimizer != TBE_OPT_ROWWISE_ADAGRAD && cfg->optimizer != TBE_OPT_ADAGRAD &&
          cfg->optimizer != TBE_OPT_ADAM) ||
         (cfg->output_dtype != TBE_DTYPE_FP32 && cfg->output_dtype != TBE_DTYPE_FP16) ||
@@ -316,6 +317,7 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
     h->optimizer = cfg->optimizer;
     h->out_dtype = cfg->output_dtype;
     h->grad_dtype = cfg->grad_dtype;
+    h->layout = cfg->layout;
     h->max_batch = cfg->max_batch;
     h->max_indices = cfg->max_indices;
     h->sumD = sumD;
@@ -635,6 +637,8 @@ static tbe_status_t enqueue_update(tbe_s* h, const void* d_grad_out, const OptCa
     a.T = h->T;
     a.sumD = (int32_t)h->sumD;
     a.dpad = (int32_t)align_up((size_t)h->dmax, 4);
+    a.batch = h->sorted_batch;
+    a.table_major = h->layout;
     a.opt.state0 = h->d_state;
     a.opt.state1 = h->optimizer == TBE_OPT_ADAM ? h->d_state + h->weight_elems : h->d_state;
     a.opt.lr = oc.lr;

@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
     const TableMeta* __restrict__ meta, const WT* __restrict__ weights,
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
     OT* __restrict__ out, const void* __restrict__ zero_row, int32_t B, int32_t num_bags,
-    int32_t sumD, int32_t n_total, int32_t bags_per_wave)
+    int32_t sumD, int32_t n_total, int32_t bags_per_wave, int32_t table_major)
 {
     using IO = RowIO<WT, EPL>;
     using Vec = typename IO::Vec;
@@ -241,7 +241,8 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
 
         if (active) {
             const int b = j - t * B + grp;
-            OT* op = out + (int64_t)b * sumD + m.col;
+            // batch-major: row b of [B, sumD] at column col; table-major: row b of the table's own [B, D] block
+            OT* op = table_major ? out + (int64_t)B * m.col + (int64_t)b * D : out + (int64_t)b * sumD + m.col;
 #pragma unroll
             for (int k = 0; k < KMAX; ++k) {
                 if (evalid[k]) {
@@ -911,6 +912,8 @@ struct BwdArgs {
     int32_t T;
     int32_t sumD;
     int32_t dpad;
+    int32_t batch;
+    int32_t table_major;   // gradient layout: 0 = [B, sumD] rows, 1 = one [B, D_t] block per table
     OptParams opt;
 };
 
@@ -1135,13 +1138,13 @@ __device__ __forceinline__ void store_partial(float* __restrict__ dst, const flo
 // G short runs at once, one per lane group; ML = longest run of the batch (1..kShortRun).
 template <typename WT, typename GT, int OPT, int ML>
 __device__ __forceinline__ void short_batch(const BwdArgs& a, WT* __restrict__ wtab, int64_t woff,
-                                            const GT* __restrict__ gb, const int32_t* __restrict__ s_val, int q0,
+                                            const GT* __restrict__ gb, int64_t sumD,
+                                            const int32_t* __restrict__ s_val, int q0,
                                             int s, int len, uint32_t key, uint32_t rbase, int D, const Cols& c,
                                             bool active)
 {
     using IO = RowIO<WT, 4>;
     using GIO = GradIO<GT>;
-    const int64_t sumD = a.sumD;
     const int64_t rel = (int64_t)(key - rbase) * D;        // key is a valid row even for idle groups
     WT* wrow = wtab + rel;
     typename IO::Vec wv[2];
@@ -1205,7 +1208,7 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     const int nruns = ue - ub;  // runs that start in [q0, q1): at most kChunk
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     const int32_t* __restrict__ vals = a.sorted_vals;
-    const int64_t sumD = a.sumD;
+    int64_t sumD = a.sumD;   // distance between the gradient rows of consecutive bags (D_t when table-major)
 
     // ---- stage run descriptors and payloads (wavefront-private LDS); straight-line clamped loads
     {
@@ -1267,7 +1270,8 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         const int e0 = a.seg_offsets[u0 + 1];
         if (e0 - s0 > kLongRun) {
             seek_table(a.unique_keys[u0]);
-            const GT* gb = grad_out + m.col;
+            const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
+            sumD = a.table_major ? m.dim : a.sumD;
             const Cols c(m.dim, m.lpr_bwd, lane);
             wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, q0, min(e0, q1),
                                 a.zero_row, c, acc);
@@ -1283,7 +1287,8 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         const int lprl = m.lpr_bwd;
         const int s0 = uniform(s_seg[r]);
         const int len0 = uniform(s_seg[r + 1]) - s0;
-        const GT* gb = grad_out + m.col;
+        const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
+        sumD = a.table_major ? m.dim : a.sumD;
         WT* wtab = weights + m.woff;
         const Cols c(D, lprl, lane);
         if (len0 > kShortRun) {
@@ -1331,10 +1336,10 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
                            (__ballot(lenc > 3) != 0ull);
             static_assert(kShortRun == 4, "short_batch is instantiated for 1..4 lookups");
             switch (ml) {
-                case 1: short_batch<WT, GT, OPT, 1>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                case 2: short_batch<WT, GT, OPT, 2>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                case 3: short_batch<WT, GT, OPT, 3>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                default: short_batch<WT, GT, OPT, 4>(a, wtab, m.woff, gb, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 1: short_batch<WT, GT, OPT, 1>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 2: short_batch<WT, GT, OPT, 2>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                case 3: short_batch<WT, GT, OPT, 3>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
+                default: short_batch<WT, GT, OPT, 4>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
             }
             r += nb;
         }

@@ -30,6 +30,8 @@ TBE_POOLING_SUM = 0
 TBE_OPT_ROWWISE_ADAGRAD = 0
 TBE_OPT_ADAGRAD = 1
 TBE_OPT_ADAM = 2
+TBE_LAYOUT_BATCH_MAJOR = 0
+TBE_LAYOUT_TABLE_MAJOR = 1
 _TORCH_DTYPE = {TBE_DTYPE_FP32: torch.float32, TBE_DTYPE_FP16: torch.float16, TBE_DTYPE_BF16: torch.bfloat16}
 
 EXPORTED = [
@@ -63,7 +65,7 @@ class tbe_config_t(ctypes.Structure):
         ("optimizer", ctypes.c_int32),
         ("output_dtype", ctypes.c_int32),
         ("grad_dtype", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("layout", ctypes.c_int32),
     ]
 
 
@@ -131,12 +133,12 @@ def _stream_ptr(stream) -> ctypes.c_void_p:
 def tbe_create(rows, dims, weight_dtype: int, max_batch: int, max_indices: int,
                pooling: int = TBE_POOLING_SUM, optimizer: int = TBE_OPT_ROWWISE_ADAGRAD,
                output_dtype: int = TBE_DTYPE_FP32, grad_dtype: int = TBE_DTYPE_FP32,
-               reserved: int = 0) -> Tuple[int, Optional[int]]:
+               layout: int = 0) -> Tuple[int, Optional[int]]:
     rows = np.ascontiguousarray(rows, np.int64)
     dims = np.ascontiguousarray(dims, np.int32)
     cfg = tbe_config_t(len(rows), rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                        dims.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), weight_dtype, pooling,
-                       max_batch, max_indices, optimizer, output_dtype, grad_dtype, reserved)
+                       max_batch, max_indices, optimizer, output_dtype, grad_dtype, layout)
     h = ctypes.c_void_p()
     rc = lib().tbe_create(ctypes.byref(cfg), ctypes.byref(h))
     return rc, (h.value if rc == TBE_OK else None)
@@ -281,7 +283,8 @@ class TableBatchedEmbeddingBags:
 
     def __init__(self, rows, dims, weight_dtype: int, max_batch: int, max_indices: int, device="cuda:0",
                  weights: Optional[torch.Tensor] = None, optimizer: int = TBE_OPT_ROWWISE_ADAGRAD,
-                 output_dtype: int = TBE_DTYPE_FP32, grad_dtype: int = TBE_DTYPE_FP32):
+                 output_dtype: int = TBE_DTYPE_FP32, grad_dtype: int = TBE_DTYPE_FP32,
+                 layout: int = TBE_LAYOUT_BATCH_MAJOR):
         self.rows = np.ascontiguousarray(rows, np.int64)
         self.dims = np.ascontiguousarray(dims, np.int32)
         self.T = len(self.rows)
@@ -291,7 +294,7 @@ class TableBatchedEmbeddingBags:
         self.grad_torch_dtype = _TORCH_DTYPE[grad_dtype]
         self.device = torch.device(device)
         rc, h = tbe_create(self.rows, self.dims, weight_dtype, max_batch, max_indices, optimizer=optimizer,
-                           output_dtype=output_dtype, grad_dtype=grad_dtype)
+                           output_dtype=output_dtype, grad_dtype=grad_dtype, layout=layout)
         if rc != TBE_OK:
             raise TbeError(rc, "tbe_create")
         self.h = h

@@ -23,10 +23,24 @@ def rtol_for(dtype: int) -> float:
     return RTOL_FP32 if dtype == 0 else RTOL_FP16
 
 
-def make_op(spec, device, max_batch=None, max_indices=None, weights=None):
+def make_op(spec, device, max_batch=None, max_indices=None, weights=None, layout=0):
     return tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype,
                                          spec.batch if max_batch is None else max_batch,
-                                         max_indices, device=device, weights=weights)
+                                         max_indices, device=device, weights=weights, layout=layout)
+
+
+def to_table_major(x: np.ndarray, dims) -> np.ndarray:
+    """[B, sumD] rows -> the flat array that holds one contiguous [B, D_t] block per table, in table order."""
+    cols = np.concatenate([[0], np.cumsum(dims)]).astype(np.int64)
+    return np.concatenate([np.ascontiguousarray(x[:, cols[t]:cols[t + 1]]).ravel() for t in range(len(dims))])
+
+
+def from_table_major(flat: np.ndarray, batch: int, dims) -> np.ndarray:
+    cols = np.concatenate([[0], np.cumsum(dims)]).astype(np.int64)
+    out = np.empty((batch, int(cols[-1])), flat.dtype)
+    for t in range(len(dims)):
+        out[:, cols[t]:cols[t + 1]] = flat[batch * cols[t]:batch * cols[t + 1]].reshape(batch, int(dims[t]))
+    return out
 
 
 def assert_forward_close(gpu_out: np.ndarray, ref_out: np.ndarray, absref: np.ndarray, what=""):
@@ -110,23 +124,28 @@ def assert_update_close(spec, ref: dict, w0: np.ndarray, m0: np.ndarray, gpu_w: 
 
 
 def full_parity_step(spec, indices: np.ndarray, offsets: np.ndarray, w0: np.ndarray, grad: np.ndarray, device,
-                     lr=0.01, eps=1e-8, m0=None, what="", check_inputs=True):
-    """One forward + one backward through the C ABI, every output compared with the oracle."""
+                     lr=0.01, eps=1e-8, m0=None, what="", check_inputs=True, layout=0):
+    """One forward + one backward through the C ABI, every output compared with the oracle.
+    With layout=1 the library writes its output and reads the gradient table-major; the oracle
+    always works on [B, sumD] rows and the conversion happens here, on the host."""
     B = spec.batch
     N = int(offsets[-1])
     if m0 is None:
         m0 = np.zeros(spec.total_rows, np.float32)
     ref = oracle_step(spec, indices, offsets, w0, m0, grad, lr, eps)
-    op = make_op(spec, device, max_indices=max(N, 1), weights=torch.from_numpy(w0.copy()).to(device))
+    op = make_op(spec, device, max_indices=max(N, 1), weights=torch.from_numpy(w0.copy()).to(device), layout=layout)
     op.state.copy_(torch.from_numpy(m0))
     d_idx = torch.from_numpy(indices).to(device)
     d_off = torch.from_numpy(offsets).to(device)
-    d_grad = torch.from_numpy(grad).to(device)
+    d_grad = torch.from_numpy(to_table_major(grad, spec.dims) if layout else grad).to(device)
     if check_inputs:
         assert op.check_inputs(d_idx, d_off, B, num_indices=N) == tbe.TBE_OK
     out = op.forward(d_idx, d_off, B, num_indices=N)
     torch.cuda.synchronize()
-    fwd_err = assert_forward_close(out.cpu().numpy(), ref["out"], ref["absref"], what)
+    h_out = out.cpu().numpy()
+    if layout:
+        h_out = from_table_major(h_out.ravel(), B, spec.dims)
+    fwd_err = assert_forward_close(h_out, ref["out"], ref["absref"], what)
     op.backward_rowwise_adagrad(d_idx, d_off, B, d_grad, lr, eps, num_indices=N)
     art = op.artifacts()
     assert_artifacts_equal(art, ref["art"], what)

@@ -51,6 +51,18 @@ def test_mixed_dims_all_lane_mappings(gpu_device, dtype):
     print("mixed", r)
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_table_major_output_and_gradient_layout(gpu_device, dtype):
+    # one contiguous [B, D_t] block per table instead of [B, sumD] rows: same numbers, other addresses;
+    # dims cover every lane mapping, the index distribution gives short, medium and long runs
+    dims = [4, 8, 12, 32, 36, 64, 100, 128, 192, 256, 260, 384, 512]
+    rows = [50, 7, 300, 1000, 33, 2000, 500, 4000, 129, 700, 90, 250, 1]
+    spec = wl.custom(rows, dims, dtype, 611, 6.0, index_dist="zipf", zipf_s=1.05, name="table-major")
+    idx, off, w, g = _np_case(spec, 6)
+    r = tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="table-major", layout=1)
+    print("table-major", r)
+
+
 def test_fp16_dims_multiple_of_8_vector_path(gpu_device):
     spec = wl.custom([3000, 500, 100], [128, 32, 256], 1, 200, [20.0, 3.0, 40.0], index_dist="zipf", name="fp16x8")
     idx, off, w, g = _np_case(spec, 9)

@@ -146,7 +146,7 @@ def test_optimizer_and_dtype_configuration():
     assert tbe.tbe_create(rows, dims, 0, 4, 100, output_dtype=tbe.TBE_DTYPE_BF16)[0] == bad
     assert tbe.tbe_create(rows, dims, 0, 4, 100, grad_dtype=3)[0] == bad
     assert tbe.tbe_create(rows, dims, tbe.TBE_DTYPE_BF16, 4, 100)[0] == bad
-    assert tbe.tbe_create(rows, dims, 0, 4, 100, reserved=1)[0] == bad
+    assert tbe.tbe_create(rows, dims, 0, 4, 100, layout=2)[0] == bad
     # entry points of another optimizer are refused before anything is enqueued (unbound handle: NOT_BOUND first)
     rc, h = tbe.tbe_create(rows, dims, 0, 4, 100, optimizer=tbe.TBE_OPT_ADAM)
     L = tbe.lib()
