@@ -37,7 +37,8 @@
  *   state             float32; row-wise AdaGrad: the moment of row r of table t is element
  *                     state_offsets[t] + r (other optimizers: see tbe_config_t)
  *   output / grad     [batch, sum_t dims[t]] row-major, float32 unless configured otherwise; table t owns columns
- *                     [out_col_offsets[t], out_col_offsets[t] + dims[t])
+ *                     [out_col_offsets[t], out_col_offsets[t] + dims[t]).  TBE_LAYOUT_TABLE_MAJOR stores the
+ *                     same values as one [batch, dims[t]] block per table instead.
  *   linear row id     key = state_offsets[t] + row  (uint32; the sort key of the backward pass)
  */
 #ifndef TBE_H_
@@ -75,9 +76,8 @@ enum { TBE_POOLING_SUM = 0 };
 enum { TBE_OPT_ROWWISE_ADAGRAD = 0, TBE_OPT_ADAGRAD = 1, TBE_OPT_ADAM = 2 };
 /* Layout of d_out and d_grad_out.  BATCH_MAJOR: one row of sumD values per sample, table t in columns
  * [c_t, c_t + D_t) -- what a sample's feature interaction consumes.  TABLE_MAJOR: one contiguous
- * [batch, D_t] block per table, table t's block starting at element batch * c_t -- what a table-wise
- * all-to-all ships per table, and the friendlier one for the backward pass, whose gradient-row gathers
- * then stay inside a few MB per table instead of striding over the whole [batch, sumD] array. */
+ * [batch, D_t] block per table, table t's block starting at element batch * c_t (batch = the call's
+ * batch, not max_batch) -- what a table-wise all-to-all ships per table.  The values are the same. */
 enum { TBE_LAYOUT_BATCH_MAJOR = 0, TBE_LAYOUT_TABLE_MAJOR = 1 };
 
 typedef struct {
@@ -137,7 +137,8 @@ TBE_API tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, v
  * Forward (Section 2 "Embedding operators", fused over tables per Section 5.1):
  *   d_out[b, c_t + d] = sum_{p in bag (t,b)} W_t[d_indices[p], d]      accumulated in fp32
  * One kernel launch for all tables.  An empty bag pools to 0.  Indices are assumed valid
- * (see tbe_check_inputs).  d_out is [batch, sumD] in the configured output type, written completely.
+ * (see tbe_check_inputs).  d_out holds batch * sumD elements of the configured output type in the
+ * configured layout and is written completely.
  * Errors: NOT_BOUND, INVALID_ARG (null, batch < 0 or > max_batch, num_indices < 0 or > max_indices), HIP.
  */
 TBE_API tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
@@ -155,7 +156,7 @@ TBE_API tbe_status_t tbe_forward(tbe_handle_t h, const int32_t* d_indices, const
  * segmented by table and reads the caller's indices directly) and run-length segmented in the
  * workspace, then every run is reduced on chip and its row updated once.
  * The integer artefacts stay in the workspace until the next backward call (tbe_backward_artifacts).
- * d_grad_out is [batch, sumD] in the configured gradient type.
+ * d_grad_out holds batch * sumD elements of the configured gradient type, laid out like d_out.
  * Errors: as tbe_forward; INVALID_ARG if the handle was created for another optimizer.
  */
 TBE_API tbe_status_t tbe_backward_rowwise_adagrad(tbe_handle_t h, const int32_t* d_indices,
