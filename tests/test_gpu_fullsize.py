@@ -51,13 +51,16 @@ def _sample_tables(spec, rng, extra=3):
     return sorted(pick)
 
 
-@pytest.mark.parametrize("k,variant", [(1, "fp32"), (2, "fp32"), (3, "fp32"), (4, "fp32"), (2, "16bit"), (4, "16bit")])
+@pytest.mark.parametrize("k,variant", [(1, "fp32"), (2, "fp32"), (3, "fp32"), (4, "fp32"), (2, "16bit"), (4, "16bit"),
+                                       (2, "table"), (3, "table")])
 def test_full_size_config(gpu_device, k, variant):
     """variant "16bit": float16 pooled output and bfloat16 upstream gradient (the oracle is fed the float32
-    values of exactly those bfloat16 numbers; the output tolerance gains one fp16 rounding)."""
+    values of exactly those bfloat16 numbers; the output tolerance gains one fp16 rounding).
+    variant "table": output and gradient in the table-major layout (one [B, D_t] block per table)."""
     dev = gpu_device
     spec = wl.config(k)
     sixteen = variant == "16bit"
+    table_major = variant == "table"
     gc.collect()
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info(dev)
@@ -72,15 +75,20 @@ def test_full_size_config(gpu_device, k, variant):
     if sixteen:
         grad = grad.to(torch.bfloat16)
     N, B, T = batch.num_indices, spec.batch, spec.T
+    cols = np.concatenate([[0], np.cumsum(spec.dims)])
+    # what the library is handed: the [B, sumD] gradient itself, or its per-table blocks one after another
+    grad_arg = grad
+    if table_major:
+        grad_arg = torch.cat([grad[:, int(cols[t]):int(cols[t + 1])].reshape(-1) for t in range(T)])
     print(f"[cfg{k}] N={N} T={T} B={B}", flush=True)
     op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, N, device=dev, weights=weights,
                                        output_dtype=tbe.TBE_DTYPE_FP16 if sixteen else tbe.TBE_DTYPE_FP32,
-                                       grad_dtype=tbe.TBE_DTYPE_BF16 if sixteen else tbe.TBE_DTYPE_FP32)
+                                       grad_dtype=tbe.TBE_DTYPE_BF16 if sixteen else tbe.TBE_DTYPE_FP32,
+                                       layout=tbe.TBE_LAYOUT_TABLE_MAJOR if table_major else tbe.TBE_LAYOUT_BATCH_MAJOR)
     assert op.check_inputs(batch.indices, batch.offsets, B, num_indices=N) == tbe.TBE_OK
 
     R = np.concatenate([[0], np.cumsum(spec.rows)])
     woffs = np.concatenate([[0], np.cumsum(spec.rows * spec.dims.astype(np.int64))])
-    cols = np.concatenate([[0], np.cumsum(spec.dims)])
     tables = _sample_tables(spec, rng)
     tab_off = batch.offsets[::B].cpu().numpy()          # positions where each table's lookups start
 
@@ -106,7 +114,11 @@ def test_full_size_config(gpu_device, k, variant):
         sub_off[1:] = np.cumsum([len(p) for p in pieces])
         ref, absref = orc.forward(np.array([len(need_rows)], np.int64), np.array([D], np.int32), spec.dtype, sub_w,
                                   inv.astype(np.int32), sub_off, len(bags), want_absref=True)
-        got = out[torch.from_numpy(bags).to(dev), int(cols[t]):int(cols[t + 1])].float().cpu().numpy()
+        if table_major:
+            out_t = out.view(-1)[B * int(cols[t]):B * int(cols[t + 1])].view(B, D)
+        else:
+            out_t = out[:, int(cols[t]):int(cols[t + 1])]
+        got = out_t[torch.from_numpy(bags).to(dev)].float().cpu().numpy()
         if sixteen:
             # one extra rounding of the fp32 sum to fp16 (2^-11 relative, 2^-25 absolute for subnormals)
             r64 = ref.astype(np.float64)
@@ -138,7 +150,7 @@ def test_full_size_config(gpu_device, k, variant):
         Wt = weights[int(woffs[t]):int(woffs[t + 1])].view(H, D)
         samples[t] = dict(rows=rows_s, w_old=Wt[torch.from_numpy(rows_s).to(dev)].cpu().numpy().copy(),
                           counts=cnt[torch.from_numpy(rows_s).to(dev)].cpu().numpy())
-    op.backward_rowwise_adagrad(batch.indices, batch.offsets, B, grad, spec.lr, spec.eps, num_indices=N)
+    op.backward_rowwise_adagrad(batch.indices, batch.offsets, B, grad_arg, spec.lr, spec.eps, num_indices=N)
     art = op.artifacts()
     U = art["num_unique"]
     print(f"[cfg{k}] backward done, U={U} ({U / N:.3f} of N)", flush=True)
