@@ -385,12 +385,23 @@ def main():
                 "logical_GBps": round(logical[dominant] / (dom_ms * 1e-3) / 1e9, 1)}
     # measured L2<->fabric bytes per launch of that kernel (two rocprofv3 --pmc runs, summarised in profiles/)
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    step_traffic = None
     if os.path.exists(traffic_file):
         for line in open(traffic_file):
             f = line.split()
-            if len(f) == 3 and f[0] == spec.name and f[1] == dominant + "_kernel":
-                roofline["traffic"] = float(f[2])
-                roofline["traffic_GBps"] = round(float(f[2]) / (dom_ms * 1e-3) / 1e9, 1)
+            if len(f) == 3 and f[0] == spec.name:
+                step_traffic = (step_traffic or 0.0) + float(f[2])
+                if f[1] == dominant + "_kernel":
+                    roofline["traffic"] = float(f[2])
+                    roofline["traffic_GBps"] = round(float(f[2]) / (dom_ms * 1e-3) / 1e9, 1)
+    # the counters were collected for the default variant only (fp32 output and gradient, [B, sumD] rows,
+    # row-wise AdaGrad, forward + backward)
+    default_variant = (args.out_dtype == "fp32" and args.grad_dtype == "fp32" and args.layout == "batch"
+                       and opt_id == tbe.TBE_OPT_ROWWISE_ADAGRAD and not args.fwd_only)
+    if not default_variant:
+        roofline["traffic"] = None
+        roofline.pop("traffic_GBps", None)
+        step_traffic = None
 
     ms_per_step = elapsed / args.steps * 1e3
     fwd_ms = kernels.get("forward", {}).get("ms_per_step", 0.0)
@@ -431,6 +442,8 @@ def main():
         "fwd_ms": fwd_ms,
         "bwd_ms": round(bwd_ms, 5),
         "step_compulsory_GBps": round(sum(comp.values()) / (ms_per_step * 1e-3) / 1e9, 1) if not args.fwd_only else None,
+        # all kernels of a step: measured L2<->fabric bytes (profiles/hbm_traffic.txt) over the step's wall time
+        "step_traffic_GBps": round(step_traffic / (ms_per_step * 1e-3) / 1e9, 1) if step_traffic else None,
         "setup_s": round(setup_s, 2),
     }
     if not args.no_cpu_baseline and opt_id == tbe.TBE_OPT_ROWWISE_ADAGRAD:
