@@ -153,3 +153,15 @@ def test_optimizer_and_dtype_configuration():
     assert L.tbe_backward_adam(h, None, None, 0, 0, None, 0.1, 0.9, 0.999, 1e-8, 1, None) == tbe.TBE_ERR_NOT_BOUND
     assert L.tbe_backward_update_adagrad(h, None, 0.1, 1e-8, None) == tbe.TBE_ERR_NOT_BOUND
     tbe.tbe_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "single-GPU" in (r.stdout + r.stderr)
+    assert not r.stdout.strip().startswith("{")     # no result line
