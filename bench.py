@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--paper-membench", choices=["fp32", "fp16"], default=None,
                     help="run the Appendix A memory-benchmark shape instead of a config")
     ap.add_argument("--batch", type=int, default=None, help="batch override (memory benchmark sweep)")
+    ap.add_argument("--zipf", type=float, default=None,
+                    help="override the configuration's index distribution: Zipf exponent, 0 = uniform (sensitivity runs)")
     ap.add_argument("--rotation", type=int, default=4, help="number of pre-generated batches")
     ap.add_argument("--flush", action="store_true", help="write a 1 GiB scratch between steps (cold caches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -243,6 +245,12 @@ def main():
         spec = wl.config(args.config)
         if args.batch:
             spec.batch = args.batch
+            spec.name += f"-B{args.batch}"
+        if args.zipf is not None:
+            # sensitivity runs: the same tables with another index distribution (0 = uniform)
+            spec.index_dist = "zipf" if args.zipf > 0 else "uniform"
+            spec.zipf_s = args.zipf
+            spec.name += f"-zipf{args.zipf:g}" if args.zipf > 0 else "-uniform"
     if args.inputs:
         bench_inputs(args, spec, dev)
         return
