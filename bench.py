@@ -411,6 +411,22 @@ def main():
         roofline.pop("traffic_GBps", None)
         step_traffic = None
 
+    # what a plain device-to-device copy reaches on this machine, as a second denominator beside the published peak
+    if args.steps >= 5:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(2):
+            dst.copy_(src)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        roofline["copy_GBps"] = round(2 * src.numel() * 4 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        roofline["frac_of_copy"] = round(achieved / roofline["copy_GBps"], 4)
+        del src, dst
+
     ms_per_step = elapsed / args.steps * 1e3
     fwd_ms = kernels.get("forward", {}).get("ms_per_step", 0.0)
     bwd_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k != "forward")
