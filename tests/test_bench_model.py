@@ -1,0 +1,37 @@
+"""The byte model behind bench.py's roofline figures, checked on a case small enough to count by hand."""
+import numpy as np
+
+import bench
+from paper_2104_05158_amd import workloads as wl
+
+
+def test_kernel_bytes_on_a_hand_counted_case():
+    # two fp16 tables, D = 8 and 16, batch 4: table 0 gets 10 lookups on 3 distinct rows, table 1 gets 6 on 6
+    spec = wl.custom([100, 50], [8, 16], 1, 4, 1.0)
+    n_t, u_t = np.array([10.0, 6.0]), np.array([3.0, 6.0])
+    comp, logical = bench.kernel_bytes(spec, n_t, u_t, np.zeros(2), np.zeros(2))
+    N, U, bags, B = 16, 9, 8, 4
+    io_fwd = N * 4 + bags * 8 + B * 4 * (8 + 16)                       # indices, offsets, fp32 output
+    assert comp["forward"] == (3 * 8 + 6 * 16) * 2 + io_fwd == 752      # each distinct row once
+    assert logical["forward"] == (10 * 8 + 6 * 16) * 2 + io_fwd == 864  # every lookup a row read
+    rmw = 3 * (2 * 8 * 2 + 8) + 6 * (2 * 16 * 2 + 8)                    # row read + write, moment read + write
+    grad_once = min(10 * 4 * 8, B * 4 * 8) + min(6 * 4 * 16, B * 4 * 16)  # a gradient row at most once per bag
+    assert comp["reduce_update"] == N * 4 + U * 8 + grad_once + rmw == 1072
+    assert logical["reduce_update"] == N * 4 + U * 8 + (10 * 4 * 8 + 6 * 4 * 16) + rmw == 1392
+    assert comp["radix_hist"] == N * 4 and comp["radix_scatter"] == N * 16
+    assert comp["runlength"] == N * 4 + U * 8
+    assert comp["long_fixup"] == 0
+
+
+def test_long_runs_add_partial_rows_and_16_bit_types_halve_the_row_bytes():
+    spec = wl.custom([1000], [64], 0, 2048, 1.0)
+    n_t, u_t = np.array([5000.0]), np.array([100.0])
+    base, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(1), np.zeros(1))
+    # one run of 1280 lookups: a partial fp32 row per 128 positions plus two ragged ends, written and read once
+    with_long, _ = bench.kernel_bytes(spec, n_t, u_t, np.array([1280.0]), np.array([1.0]))
+    rows = 1280 / 128 + 2
+    assert with_long["reduce_update"] - base["reduce_update"] == rows * 4 * 64
+    assert with_long["long_fixup"] == rows * 4 * 64 + (2 * 64 * 4 + 8)
+    half, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(1), np.zeros(1), so=2, sg=2)
+    assert base["forward"] - half["forward"] == 2048 * 2 * 64
+    assert base["reduce_update"] - half["reduce_update"] == min(5000, 2048) * 2 * 64
