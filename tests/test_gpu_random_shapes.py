@@ -43,3 +43,16 @@ def test_random_shape(gpu_device, seed):
                             what=f"rnd{seed}", layout=layout)
     print(f"rnd{seed}: T={spec.T} B={spec.batch} dims={spec.dims.tolist()} rows={spec.rows.tolist()} "
           f"dtype={spec.dtype} layout={layout} {r}")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shape_other_optimizers_and_gradient_types(gpu_device, seed):
+    # the same random shapes through element-wise AdaGrad / lazy Adam (two steps each), with the gradient in
+    # float32, float16 or bfloat16
+    import test_gpu_optimizers as tgo
+    from paper_2104_05158_amd import tbe
+
+    spec, _ = _random_spec(seed)
+    optimizer = tbe.TBE_OPT_ADAM if seed % 2 else tbe.TBE_OPT_ADAGRAD
+    grad_dtype = [tbe.TBE_DTYPE_FP32, tbe.TBE_DTYPE_FP16, tbe.TBE_DTYPE_BF16][seed % 3]
+    tgo._run(spec, optimizer, grad_dtype, gpu_device, steps=2, seed=500 + seed)
