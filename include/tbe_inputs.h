@@ -40,6 +40,22 @@ TBE_API tbe_status_t tbe_lengths_to_offsets(const int32_t* d_lengths, int64_t nu
                                             void* d_scratch, size_t scratch_bytes, void* stream);
 
 /*
+ * tbe_lengths_to_offsets for callers that can neither allocate nor pass a scratch buffer: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * tbe_lengths_to_offsets, same kernels; the per-tile block sums of the scan live in a fixed 1 MiB
+ * array inside the library's device image (one copy per GPU, held until the process ends), so the
+ * call allocates nothing and takes no scratch argument.
+ * Limit: num_bags <= tbe_lengths_to_offsets_noalloc_max_bags() (536,866,816); larger -> TBE_ERR_UNSUPPORTED.
+ * All calls on one GPU share that array: two calls that overlap in time on the same GPU (different
+ * streams, or different host threads) race and give wrong offsets; order them on one stream.
+ * Nothing in the array has to start at zero (every entry that is read is written first by the same call).
+ * Errors: TBE_ERR_INVALID_ARG as tbe_lengths_to_offsets, TBE_ERR_HIP if the array's address cannot be obtained.
+ */
+TBE_API tbe_status_t tbe_lengths_to_offsets_noalloc(const int32_t* d_lengths, int64_t num_bags,
+                                                    int64_t* d_offsets, void* stream);
+TBE_API int64_t tbe_lengths_to_offsets_noalloc_max_bags(void);
+
+/*
  * Section 7.1: (W, T, B) -> (T, W, B).  Input bag (w,t,b) has id (w*T + t)*B + b, output bag
  * (t,w,b) has id (t*W + w)*B + b; every bag moves with its indices as a block, order kept:
  *   d_lengths_out[(t,w,b)] = d_lengths_in[(w,t,b)];  d_offsets_out = prefix sum of d_lengths_out;

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "tbe_inputs_kernels.hip.h"
 
@@ -43,6 +44,35 @@ tbe_status_t check_scratch(const void* d_scratch, size_t bytes, int64_t num_bags
 {
     if (!d_scratch || misaligned(d_scratch, 256) || bytes < scratch_bytes(num_bags))
         return TBE_ERR_INVALID_ARG;
+    return TBE_OK;
+}
+
+// Scratch of tbe_lengths_to_offsets_noalloc: the per-tile block sums of the scan live in this array
+// instead of a caller-provided buffer.  Every GPU the library runs on holds its own copy at its own
+// address; host code never uses the array's name as an address, only the pointer that
+// hipGetSymbolAddress returned for the current device.
+constexpr int64_t kNoAllocMaxTiles = 131071;                         // (1 MiB / 8) - 1 block sums
+constexpr int64_t kNoAllocMaxBags = kNoAllocMaxTiles * kScanTile;    // 536,866,816 bags
+static __device__ __align__(256) unsigned char scratch[(kNoAllocMaxTiles + 1) * 8];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// device address of `scratch` on the current device (looked up once per device)
+tbe_status_t noalloc_scratch(int64_t** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return TBE_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return TBE_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<int64_t*>(g_scratch_ptr[dev]);
     return TBE_OK;
 }
 
@@ -84,6 +114,24 @@ tbe_status_t tbe_lengths_to_offsets(const int32_t* d_lengths, int64_t num_bags, 
         return rc;
     const Scratch s = carve(d_scratch, num_bags);
     return enqueue_scan(d_lengths, num_bags, d_offsets, s.block_sums, static_cast<hipStream_t>(stream));
+}
+
+int64_t tbe_lengths_to_offsets_noalloc_max_bags(void) { return kNoAllocMaxBags; }
+
+tbe_status_t tbe_lengths_to_offsets_noalloc(const int32_t* d_lengths, int64_t num_bags, int64_t* d_offsets,
+                                            void* stream)
+{
+    if (num_bags < 0 || !d_offsets || (num_bags > 0 && !d_lengths) || misaligned(d_lengths, 16) ||
+        misaligned(d_offsets, 16))
+        return TBE_ERR_INVALID_ARG;
+    if (num_bags > kNoAllocMaxBags)
+        return TBE_ERR_UNSUPPORTED;
+    int64_t* block_sums = nullptr;
+    tbe_status_t rc = noalloc_scratch(&block_sums);
+    if (rc != TBE_OK)
+        return rc;
+    // every block sum the scan reads is written by its first kernel in the same call: nothing has to be cleared
+    return enqueue_scan(d_lengths, num_bags, d_offsets, block_sums, static_cast<hipStream_t>(stream));
 }
 
 tbe_status_t tbe_permute_wtb_to_twb(int32_t W, int32_t T, int32_t B, const int32_t* d_lengths_in,

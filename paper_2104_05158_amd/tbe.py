@@ -44,6 +44,7 @@ EXPORTED = [
 # include/tbe_inputs.h
 EXPORTED_INPUTS = [
     "tbe_inputs_scratch_bytes", "tbe_lengths_to_offsets", "tbe_permute_wtb_to_twb", "tbe_bucketize_rowwise",
+    "tbe_lengths_to_offsets_noalloc", "tbe_lengths_to_offsets_noalloc_max_bags",
 ]
 
 
@@ -101,11 +102,14 @@ def lib() -> ctypes.CDLL:
         sz = ctypes.c_size_t
         L.tbe_inputs_scratch_bytes.argtypes = [i64]
         L.tbe_lengths_to_offsets.argtypes = [vp, i64, vp, vp, sz, vp]
+        L.tbe_lengths_to_offsets_noalloc.argtypes = [vp, i64, vp, vp]
+        L.tbe_lengths_to_offsets_noalloc_max_bags.argtypes = []
         L.tbe_permute_wtb_to_twb.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, vp, vp, sz, vp]
         L.tbe_bucketize_rowwise.argtypes = [i32, i32, i32, vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
         for name in EXPORTED + EXPORTED_INPUTS:
             getattr(L, name).restype = ctypes.c_int
         L.tbe_inputs_scratch_bytes.restype = sz
+        L.tbe_lengths_to_offsets_noalloc_max_bags.restype = i64
         L.tbe_status_string.argtypes = [ctypes.c_int]
         L.tbe_status_string.restype = ctypes.c_char_p
         L.tbe_last_hip_error.argtypes = [vp]
@@ -254,6 +258,14 @@ def tbe_inputs_scratch_bytes(num_bags: int) -> int:
 def tbe_lengths_to_offsets(lengths, num_bags: int, offsets, scratch, stream=None) -> int:
     return lib().tbe_lengths_to_offsets(_ptr(lengths), num_bags, _ptr(offsets), _ptr(scratch), _nbytes(scratch),
                                         _stream_ptr(stream))
+
+
+def tbe_lengths_to_offsets_noalloc(lengths, num_bags: int, offsets, stream=None) -> int:
+    return lib().tbe_lengths_to_offsets_noalloc(_ptr(lengths), num_bags, _ptr(offsets), _stream_ptr(stream))
+
+
+def tbe_lengths_to_offsets_noalloc_max_bags() -> int:
+    return int(lib().tbe_lengths_to_offsets_noalloc_max_bags())
 
 
 def tbe_permute_wtb_to_twb(W: int, T: int, B: int, lengths_in, indices_in, num_indices: int, lengths_out,
