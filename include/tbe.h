@@ -82,7 +82,7 @@ enum { TBE_LAYOUT_BATCH_MAJOR = 0, TBE_LAYOUT_TABLE_MAJOR = 1 };
 
 typedef struct {
     int32_t num_tables;     /* T >= 1 */
-    const int64_t* rows;    /* host int64[T], each > 0, sum < 2^32 - 1 */
+    const int64_t* rows;    /* host int64[T], each in [1, 2^31), sum < 2^32 - 1 */
     const int32_t* dims;    /* host int32[T], each a multiple of 4 in [4, 512] (Table 3 reports 4..384) */
     int32_t weight_dtype;   /* TBE_DTYPE_FP32, or TBE_DTYPE_FP16 storage with fp32 accumulation */
     int32_t pooling;        /* TBE_POOLING_SUM is the only mode */
@@ -104,7 +104,8 @@ typedef struct {
  * Creates a handle (host only; copies the config arrays).  Section 5.1: one handle stands for all
  * tables that are fused into one operator on this GPU.
  * Errors: INVALID_ARG (null, T < 1, rows/dims not positive, negative sizes),
- *         UNSUPPORTED (dim not a multiple of 4 or > 512, sum of rows >= 2^32 - 1, sizes too large,
+ *         UNSUPPORTED (dim not a multiple of 4 or > 512, a table of 2^31 rows or more (indices are int32),
+ *         sum of rows >= 2^32 - 1, sizes too large,
  *         unknown dtype/pooling/optimizer/layout, BF16 tables or BF16 output).
  */
 TBE_API tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle);
@@ -192,6 +193,8 @@ TBE_API tbe_status_t tbe_backward_adam(tbe_handle_t h, const int32_t* d_indices,
  * (Sections 5.1, 5.2) for the batch sorted last; the caller must order it after that sort (same
  * stream, or an event) and must not start the next sort of this handle before it has finished:
  * both use the handle's workspace.  tbe_backward_<optimizer> is exactly these two in a row.
+ * An update may be repeated for the same sort (each call applies one more optimizer step for that
+ * batch with the gradient it is given); the sort's artefacts are not consumed.
  * Errors: as tbe_forward; update without a preceding sort returns INVALID_ARG.
  */
 TBE_API tbe_status_t tbe_backward_sort(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
@@ -220,7 +223,10 @@ TBE_API tbe_status_t tbe_backward_artifacts(tbe_handle_t h, const uint32_t** d_s
 /*
  * Slow, synchronising validator of a batch: offsets start at 0, never decrease and end at
  * num_indices; every index lies inside its table.  Returns INDEX_OUT_OF_RANGE or INVALID_ARG
- * (bad offsets) instead of letting the hot path read out of bounds.
+ * (bad offsets) instead of letting the hot path read out of bounds.  It keeps its result flag in a
+ * workspace word of its own and touches nothing else there, so it may be called between
+ * tbe_backward_sort and the update; like every call on a handle it must be ordered on the stream
+ * with the handle's other work.
  */
 TBE_API tbe_status_t tbe_check_inputs(tbe_handle_t h, const int32_t* d_indices, const int64_t* d_offsets,
                               int64_t num_indices, int32_t batch, void* stream);

@@ -280,6 +280,9 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
     for (int t = 0; t < cfg->num_tables; ++t)
         if (cfg->rows[t] <= 0 || cfg->dims[t] <= 0)
             return TBE_ERR_INVALID_ARG;
+    for (int t = 0; t < cfg->num_tables; ++t)
+        if (cfg->rows[t] >= ((int64_t)1 << 31))   // indices are int32: such a table could not be addressed
+            return TBE_ERR_UNSUPPORTED;
     if ((cfg->weight_dtype != TBE_DTYPE_FP32 && cfg->weight_dtype != TBE_DTYPE_FP16) ||
         cfg->pooling != TBE_POOLING_SUM || (cfg->layout != TBE_LAYOUT_BATCH_MAJOR && cfg->layout != TBE_LAYOUT_TABLE_MAJOR) ||
         (cfg->optimizer != TBE_OPT_ROWWISE_ADAGRAD && cfg->optimizer != TBE_OPT_ADAGRAD &&
@@ -464,8 +467,8 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
     h->sorted_n = n;
     h->sorted_batch = batch;
     if (batch == 0 || n == 0) {
-        hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(1), 0, st, counters);
-        TBE_LAUNCH_CHECK(h, "clear_counters_kernel");
+        hipLaunchKernelGGL(clear_num_unique_kernel, dim3(1), dim3(1), 0, st, counters);
+        TBE_LAUNCH_CHECK(h, "clear_num_unique_kernel");
         h->final_buf = 0;
         return TBE_OK;
     }
@@ -794,7 +797,7 @@ tbe_status_t tbe_check_inputs(tbe_handle_t h, const int32_t* d_indices, const in
     std::memset(&host, 0, sizeof(host));
     if (num_bags == 0)
         return num_indices == 0 ? TBE_OK : TBE_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(1), 0, st, counters);
+    hipLaunchKernelGGL(clear_check_flags_kernel, dim3(1), dim3(1), 0, st, counters);
     hipLaunchKernelGGL(check_inputs_kernel, dim3((unsigned)ceil_div(num_bags, 256)), dim3(256), 0, st,
                        h->ws<TableMeta>(h->off_meta), h->ws<uint32_t>(h->off_rowbase), d_indices, d_offsets,
                        num_indices, batch, num_bags, counters);

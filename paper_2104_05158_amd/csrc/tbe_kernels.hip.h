@@ -51,10 +51,15 @@ struct TableMeta {      // 32 bytes, one per table, in the workspace head
 };
 
 struct Counters {       // workspace scalars
-    int64_t num_unique;
+    int64_t num_unique;         // written by the run-length pass of every sort
+    // Number of long runs queued by the update kernel for the fix-up kernel.  Zero between update
+    // launches: the last workgroup of the fix-up kernel to finish clears it (and fixup_done), so every
+    // update starts from an empty queue -- also a second update after one sort, and every replay of a
+    // captured graph.
     uint32_t long_count;
-    uint32_t check_flags;
-    uint32_t pad[4];
+    uint32_t fixup_done;        // workgroups of the running fix-up kernel that have finished
+    uint32_t check_flags;       // written only by tbe_check_inputs
+    uint32_t pad[3];
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -332,10 +337,8 @@ __global__ __launch_bounds__(256) void sort_plan_tables_kernel(const int64_t* __
                                                                Counters* __restrict__ counters)
 {
     __shared__ uint32_t s_wave[4];
-    if (threadIdx.x == 0) {
+    if (threadIdx.x == 0)
         counters->num_unique = 0;
-        counters->long_count = 0;
-    }
     uint32_t carry = 0;
     for (int base = 0; base < T; base += 256) {
         const int t = base + threadIdx.x;
@@ -1382,6 +1385,17 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
                                0, k1 - k0 + 1, a.zero_row, c, acc);
         optimizer_epilogue<WT, OPT>(wrow, wvv, acc, m.dim, c, c.grp == 0, a.opt, key, wel, st);
     }
+    // Leave the queue empty for the next update launch.  Every wavefront read the count before its
+    // loop (the loop bound depends on it), the barrier orders those reads before this workgroup's
+    // arrival, and only the workgroup that arrives last -- after all others have arrived -- clears.
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t arrived = atomicAdd(&a.counters->fixup_done, 1u);
+        if (arrived == gridDim.x - 1) {
+            a.counters->long_count = 0;
+            a.counters->fixup_done = 0;
+        }
+    }
 }
 
 // ---------------------------------------------------------------- input validation (slow path)
@@ -1413,11 +1427,8 @@ __global__ __launch_bounds__(256) void check_inputs_kernel(
         atomicOr(&counters->check_flags, flags);
 }
 
-__global__ void clear_counters_kernel(Counters* counters)
-{
-    counters->num_unique = 0;
-    counters->long_count = 0;
-    counters->check_flags = 0;
-}
+__global__ void clear_num_unique_kernel(Counters* counters) { counters->num_unique = 0; }
+
+__global__ void clear_check_flags_kernel(Counters* counters) { counters->check_flags = 0; }
 
 }  // namespace tbe

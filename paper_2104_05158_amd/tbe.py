@@ -388,6 +388,17 @@ class TableBatchedEmbeddingBags:
         if rc != TBE_OK:
             raise TbeError(rc, "tbe_backward_update_rowwise_adagrad", tbe_last_hip_error(self.h))
 
+    def backward_update_adagrad(self, grad_out, lr: float, eps: float, stream=None):
+        rc = tbe_backward_update_adagrad(self.h, grad_out, lr, eps, stream)
+        if rc != TBE_OK:
+            raise TbeError(rc, "tbe_backward_update_adagrad", tbe_last_hip_error(self.h))
+
+    def backward_update_adam(self, grad_out, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                             stream=None):
+        rc = tbe_backward_update_adam(self.h, grad_out, lr, beta1, beta2, eps, step, stream)
+        if rc != TBE_OK:
+            raise TbeError(rc, "tbe_backward_update_adam", tbe_last_hip_error(self.h))
+
     def check_inputs(self, indices, offsets, batch: int, num_indices: Optional[int] = None) -> int:
         n = indices.numel() if num_indices is None else num_indices
         return tbe_check_inputs(self.h, indices, offsets, n, batch)

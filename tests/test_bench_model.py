@@ -35,3 +35,20 @@ def test_long_runs_add_partial_rows_and_16_bit_types_halve_the_row_bytes():
     half, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(1), np.zeros(1), so=2, sg=2)
     assert base["forward"] - half["forward"] == 2048 * 2 * 64
     assert base["reduce_update"] - half["reduce_update"] == min(5000, 2048) * 2 * 64
+
+
+def test_sort_bytes_per_launch_follow_the_tables_pass_counts():
+    # 300 rows -> 9 bits -> 2 passes; 70000 rows -> 17 bits -> 3 passes
+    assert bench.sort_passes([300, 70000, 256, 2 ** 24, 2 ** 24 + 1]).tolist() == [2, 3, 1, 3, 4]
+    spec = wl.custom([300, 70000], [8, 16], 1, 4, 1.0)
+    n_t, u_t = np.array([10.0, 6.0]), np.array([3.0, 6.0])
+    comp, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(2), np.zeros(2), passes_t=bench.sort_passes(spec.rows))
+    # three launches; the first pass of a table moves 12 bytes per lookup (index in, key + payload out), later ones 16
+    assert comp["radix_scatter"] == (10 * (12 + 16) + 6 * (12 + 32)) / 3
+    assert comp["radix_hist"] == (10 * 4 * 2 + 6 * 4 * 3) / 3
+
+
+def test_default_invocation_is_config_4_with_3_and_2_alongside():
+    a = bench.parse_args([])
+    assert a.config is None and a.others is None and a.gpus == 1
+    assert bench.parse_args(["--config", "2"]).config == 2

@@ -58,6 +58,10 @@ def test_create_validates_config():
     assert ok([10], [8], 0, 4, 100, pooling=1) == tbe.TBE_ERR_UNSUPPORTED
     assert ok([2 ** 31, 2 ** 31], [8, 8], 0, 4, 100) == tbe.TBE_ERR_UNSUPPORTED   # 2^32 rows
     assert ok([10], [8], 0, 4, 2 ** 31) == tbe.TBE_ERR_UNSUPPORTED
+    # indices are int32: a single table of 2^31 rows or more cannot be addressed, whatever the sum is
+    assert ok([2 ** 31], [8], 0, 4, 100) == tbe.TBE_ERR_UNSUPPORTED
+    assert ok([5, 2 ** 31 + 7], [8, 8], 1, 4, 100) == tbe.TBE_ERR_UNSUPPORTED
+    assert ok([2 ** 31 - 1], [8], 0, 4, 100) == tbe.TBE_OK
     assert ok([10] * 4, [8] * 4, 0, 2 ** 30, 100) == tbe.TBE_ERR_UNSUPPORTED     # T*B overflows
     assert tbe.lib().tbe_create(None, None) == tbe.TBE_ERR_INVALID_ARG
     assert tbe.tbe_destroy(None) == tbe.TBE_OK

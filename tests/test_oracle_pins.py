@@ -93,7 +93,7 @@ def test_handworked_example():
 def _dense_reference(spec, indices, offsets, weights, grad, moments0, lr, eps):
     """Count-matrix formulation: out_t = C_t W_t, G_t = C_t^T grad_t, C_t[b,r] = multiplicity."""
     T, B = spec.T, spec.batch
-    outs, new_w, new_m = [], [], []
+    outs, new_w, new_m, absrefs, Gs, Gabss = [], [], [], [], [], []
     woff = col = R = 0
     for t in range(T):
         H, D = int(spec.rows[t]), int(spec.dims[t])
@@ -103,8 +103,11 @@ def _dense_reference(spec, indices, offsets, weights, grad, moments0, lr, eps):
             for p in range(offsets[t * B + b], offsets[t * B + b + 1]):
                 C[b, indices[p]] += 1.0
         outs.append(C @ W)
+        absrefs.append(C @ np.abs(W))                 # sum of |terms| of every pooled value
         G = C.T @ grad[:, col:col + D].astype(np.float64)
         touched = C.sum(0) > 0
+        Gs.append(G[touched].ravel())                 # touched rows ascend, tables in order = unique-key order
+        Gabss.append((C.T @ np.abs(grad[:, col:col + D].astype(np.float64)))[touched].ravel())
         m = moments0[R:R + H].astype(np.float64).copy()
         m[touched] += (G[touched] ** 2).mean(1)
         Wn = W.copy()
@@ -114,7 +117,8 @@ def _dense_reference(spec, indices, offsets, weights, grad, moments0, lr, eps):
         woff += H * D
         col += D
         R += H
-    return np.concatenate(outs, 1), np.concatenate(new_w), np.concatenate(new_m)
+    extra = dict(absref=np.concatenate(absrefs, 1), G=np.concatenate(Gs), Gabs=np.concatenate(Gabss))
+    return np.concatenate(outs, 1), np.concatenate(new_w), np.concatenate(new_m), extra
 
 
 @pytest.mark.parametrize("seed", range(12))
@@ -124,10 +128,13 @@ def test_dense_brute_force(seed, dtype):
     rng = np.random.default_rng(seed)
     m0 = rng.uniform(0, 2, spec.total_rows).astype(np.float32) * (seed % 3 != 0)
     lr, eps = float(np.float32(0.05)), float(np.float32(1e-8))
-    ref_out, ref_w, ref_m = _dense_reference(spec, idx, off, w, grad, m0, lr, eps)
+    ref_out, ref_w, ref_m, extra = _dense_reference(spec, idx, off, w, grad, m0, lr, eps)
     out, absref = orc.forward(spec.rows, spec.dims, dtype, w, idx, off, spec.batch, want_absref=True)
     np.testing.assert_allclose(out, ref_out.astype(np.float32), rtol=0, atol=0)
     assert np.all(absref + 1e-12 >= np.abs(ref_out))
+    # the scale every GPU forward comparison divides by is exactly |C| . |W| (sums of a few fp64 terms:
+    # equal up to the order of the additions)
+    np.testing.assert_allclose(absref, extra["absref"], rtol=1e-14, atol=0)
     w2, m2 = w.copy(), m0.copy()
     det = orc.backward_rowwise_adagrad(spec.rows, spec.dims, dtype, w2, m2, idx, off, spec.batch, grad, lr, eps,
                                        want_detail=True)
@@ -136,6 +143,11 @@ def test_dense_brute_force(seed, dtype):
     assert np.array_equal(w2, ref_w.astype(wdt))
     # detail outputs are consistent with the update that was applied
     assert det.g_offsets[-1] == det.G.size and np.all(det.Gabs + 1e-12 >= np.abs(det.G))
+    # the per-row aggregated gradient and the scale of every GPU update comparison are exactly
+    # C^T . grad and C^T . |grad|, in unique-key order
+    assert det.G.size == extra["G"].size
+    np.testing.assert_allclose(det.G, extra["G"], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(det.Gabs, extra["Gabs"], rtol=1e-14, atol=0)
 
 
 # ---------------------------------------------------------------- P2 torch embedding_bag + autograd
