@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -31,14 +32,17 @@ enum Slot {
     SLOT_RADIX_SCATTER,
     SLOT_RUNLENGTH,
     SLOT_REDUCE_UPDATE,
+    SLOT_DENSE_ROWS,
     SLOT_LONG_FIXUP,
     SLOT_COUNT
 };
 const char* const kSlotNames[SLOT_COUNT] = {"forward",       "sort_plan",  "radix_hist",    "radix_scan",
-                                            "radix_scatter", "runlength",  "reduce_update", "long_fixup"};
+                                            "radix_scatter", "runlength",  "reduce_update", "dense_rows", "long_fixup"};
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+constexpr int kDenseGrid = 1024;   // persistent workgroups of dense_rows_kernel: 4 per CU, a multiple of 8
+
 inline int pow2ceil_log2(int x)
 {
     int l = 0;
@@ -82,6 +86,8 @@ struct tbe_s {
     int64_t max_tiles = 1;
     size_t off_hist = 0, off_scan_tmp = 0, off_rl_counts = 0, off_chunk_first = 0, off_partials = 0;
     size_t off_long_list = 0, off_zero = 0, workspace_bytes = 0;
+    size_t off_dense_dirty = 0, off_dense_cnt = 0, off_dense_list = 0, off_drun = 0, off_dgroup = 0, off_dbounds = 0;
+    int64_t dbounds_cap = 0;   // entries
     size_t weight_bytes = 0, state_bytes = 0;
 
     // bound buffers
@@ -151,6 +157,25 @@ tbe_status_t hip_fail(tbe_s* h, hipError_t e, const char* what)
             return hip_fail((h), e_, what);        \
     } while (0)
 
+// Dense hot rows: the run-length threshold for a call with `batch` bags per table.  About one lookup per
+// 12 bags is where summing counts x gradient block becomes cheaper than one gathered row per lookup; the
+// third term keeps the partial rows of a dense run (one per kDenseSlice bags) inside the slots of the
+// chunks that run covers completely (two per chunk).
+int dense_threshold(int64_t batch)
+{
+    const int64_t nslices = ceil_div(std::max<int64_t>(batch, 1), kDenseSlice);
+    return (int)std::max<int64_t>({kDenseMinRun, batch / 12, (int64_t)kChunk * ((nslices + 1) / 2 + 3)});
+}
+
+// entries of the bounds table a call with n lookups and `batch` bags per table can need
+int64_t dense_bounds_entries(int64_t n, int64_t batch, int T)
+{
+    if (batch <= 0)
+        return 0;
+    const int64_t runs = n / dense_threshold(batch) + 1;
+    return runs * (ceil_div(batch, kDenseSub) + 1);
+}
+
 void plan_workspace(tbe_s* h)
 {
     const int64_t nmax = h->max_indices;
@@ -187,6 +212,23 @@ void plan_workspace(tbe_s* h)
     const int dpad = (int)align_up((size_t)h->dmax, 4);
     h->off_partials = take(4 * (size_t)chunks * 2 * (size_t)dpad);
     h->off_long_list = take(4 * (size_t)(nmax / kLongRun + 2));
+    // dense hot rows: per-table queues, compact run list, groups, and the runs' positions at every
+    // kDenseSub-th bag.  The threshold is never below kDenseMinRun, which bounds the number of dense runs.
+    const int64_t dense_runs_max = nmax / kDenseMinRun + h->T + 2;
+    h->off_dense_cnt = take(4 * (size_t)h->T);
+    h->off_dense_dirty = take(4 * (size_t)h->T);
+    h->off_dense_list = take(4 * (size_t)dense_runs_max);
+    h->off_drun = take(4 * (size_t)dense_runs_max);
+    h->off_dgroup = take(sizeof(DenseGroup) * (size_t)(dense_runs_max / kDenseRows + h->T + 1));
+    h->dbounds_cap = 0;
+    for (int64_t b = 1;; b *= 2) {     // the need is largest at one end of a range of batch sizes: probe them all
+        const int64_t bb = std::min<int64_t>(b, h->max_batch);
+        for (int64_t cand : {bb, std::min<int64_t>(h->max_batch, 12288), std::min<int64_t>(h->max_batch, 3 * bb / 2)})
+            h->dbounds_cap = std::max(h->dbounds_cap, dense_bounds_entries(nmax, cand, h->T));
+        if (b >= h->max_batch)
+            break;
+    }
+    h->off_dbounds = take(4 * (size_t)h->dbounds_cap);
     h->workspace_bytes = off;
 }
 
@@ -426,6 +468,8 @@ tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_w
                                hipMemcpyHostToDevice));
     TBE_HIP_CHECK(h, hipMemcpy(h->d_ws + h->off_counters, &zero, sizeof(zero), hipMemcpyHostToDevice));
     TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_zero, 0, kZeroRowBytes));
+    TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_dense_cnt, 0, 4 * (size_t)h->T));
+    TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_dense_dirty, 0, 4 * (size_t)h->T));
     TBE_HIP_CHECK(h, hipDeviceSynchronize());
     h->bound = true;
     h->final_buf = -1;
@@ -569,9 +613,23 @@ static void launch_update(const BwdArgs& a, dim3 grid, dim3 grid_fix, hipStream_
         ScopedTimer tm(h, SLOT_REDUCE_UPDATE, st);
         hipLaunchKernelGGL((reduce_update_kernel<WT, GT, OPT>), grid, dim3(kBwdThreads), 0, st, a);
     }
+    if (a.dense_thr != INT32_MAX) {
+        // the runs the update kernel queued as dense: plan -> bag-range positions -> counts x gradient block
+        ScopedTimer tm(h, SLOT_DENSE_ROWS, st);
+        DenseArgs d;
+        d.b = a;
+        d.drun = h->ws<uint32_t>(h->off_drun);
+        d.dgroup = h->ws<DenseGroup>(h->off_dgroup);
+        d.dbounds = h->ws<int32_t>(h->off_dbounds);
+        d.nsub = (int32_t)ceil_div(a.batch, kDenseSub);
+        hipLaunchKernelGGL(dense_plan_kernel, dim3(1), dim3(256), 0, st, a, h->ws<uint32_t>(h->off_drun),
+                           h->ws<DenseGroup>(h->off_dgroup));
+        hipLaunchKernelGGL(dense_bounds_kernel, dim3(512), dim3(256), 0, st, d);
+        hipLaunchKernelGGL((dense_rows_kernel<GT>), dim3(kDenseGrid), dim3(kDenseThreads), 0, st, d);
+    }
     {
         ScopedTimer tm(h, SLOT_LONG_FIXUP, st);
-        hipLaunchKernelGGL((long_run_fixup_kernel<WT, OPT>), grid_fix, dim3(kBwdThreads), 0, st, a);
+        hipLaunchKernelGGL((long_run_fixup_kernel<WT, GT, OPT>), grid_fix, dim3(kBwdThreads), 0, st, a);
     }
 }
 
@@ -642,6 +700,16 @@ static tbe_status_t enqueue_update(tbe_s* h, const void* d_grad_out, const OptCa
     a.dpad = (int32_t)align_up((size_t)h->dmax, 4);
     a.batch = h->sorted_batch;
     a.table_major = h->layout;
+    // dense hot rows: only when a run can exceed the threshold and the bounds table of this call fits
+    const int thr = dense_threshold(h->sorted_batch);
+    const bool dense_on = n > thr && dense_bounds_entries(n, h->sorted_batch, h->T) <= h->dbounds_cap &&
+                          n / thr + h->T + 2 <= h->max_indices / kDenseMinRun + h->T + 2;
+    a.dense_thr = dense_on ? thr : INT32_MAX;
+    a.dense_slices = (int32_t)ceil_div(std::max(h->sorted_batch, 1), kDenseSlice);
+    a.tstart = h->ws<int32_t>(h->off_tstart);
+    a.dense_cnt = h->ws<uint32_t>(h->off_dense_cnt);
+    a.dense_list = h->ws<uint32_t>(h->off_dense_list);
+    a.dense_dirty = h->ws<uint32_t>(h->off_dense_dirty);
     a.opt.state0 = h->d_state;
     a.opt.state1 = h->optimizer == TBE_OPT_ADAM ? h->d_state + h->weight_elems : h->d_state;
     a.opt.lr = oc.lr;

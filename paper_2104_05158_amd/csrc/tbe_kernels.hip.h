@@ -38,6 +38,12 @@ constexpr int kBwdThreads = 256;          // 4 wavefronts = 4 chunks per workgro
 constexpr int kBwdUnroll = 4;             // gradient rows in flight per lane group (long runs)
 constexpr int kShortRun = 4;              // runs up to this length are handled one per lane group
 constexpr int kMaxDim = 512;
+// dense hot rows: runs longer than the call's dense threshold are summed as (count matrix) x (gradient block)
+constexpr int kDenseRows = 32;            // most runs per group: they share one pass over the table's gradient block
+constexpr int kDenseSub = 256;            // bags per count table held in LDS
+constexpr int kDenseSlice = 4 * kDenseSub;  // bags per work unit = per partial row of a dense run
+constexpr int kDenseThreads = 256;
+constexpr int kDenseMinRun = 1024;        // no run of this length or less is ever treated as dense
 constexpr int kZeroRowBytes = 4096;        // a row of zeros in the workspace (largest row: 512 x fp32 = 2 KiB)
 
 struct TableMeta {      // 32 bytes, one per table, in the workspace head
@@ -59,7 +65,9 @@ struct Counters {       // workspace scalars
     uint32_t long_count;
     uint32_t fixup_done;        // workgroups of the running fix-up kernel that have finished
     uint32_t check_flags;       // written only by tbe_check_inputs
-    uint32_t pad[3];
+    uint32_t dense_runs;        // written by dense_plan_kernel: dense runs / groups of this update
+    uint32_t dense_groups;
+    uint32_t pad[1];
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -212,12 +220,18 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
             evalid[k] = e0 < D;
             eoff[k] = min(e0, D - EPL);
         }
-        float acc[KMAX][EPL];
+        // fp32 tables: one accumulator per load slot, added pairwise at the end -- the rounding error of a
+        // long bag grows with the number of terms each accumulator sees.  (Sums of fp16 values in fp32 are
+        // exact for thousands of terms: one accumulator.)
+        constexpr int NACC = sizeof(WT) == 4 ? kFwdUnroll : 1;
+        float accs[NACC][KMAX][EPL];
 #pragma unroll
-        for (int k = 0; k < KMAX; ++k)
+        for (int q = 0; q < NACC; ++q)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e)
-                acc[k][e] = 0.f;
+            for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e)
+                    accs[q][k][e] = 0.f;
 
         if (__ballot(len > 0) != 0ull) {
             int idx[kFwdUnroll];
@@ -240,9 +254,19 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
                 for (int u = 0; u < kFwdUnroll; ++u)
 #pragma unroll
                     for (int k = 0; k < KMAX; ++k)
-                        IO::add(acc[k], raw[u][k]);
+                        IO::add(accs[u % NACC][k], raw[u][k]);
             }
         }
+        float acc[KMAX][EPL];
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                if (NACC == 4)
+                    acc[k][e] = (accs[0][k][e] + accs[1 % NACC][k][e]) + (accs[2 % NACC][k][e] + accs[3 % NACC][k][e]);
+                else
+                    acc[k][e] = accs[0][k][e];
+            }
 
         if (active) {
             const int b = j - t * B + grp;
@@ -917,6 +941,13 @@ struct BwdArgs {
     int32_t dpad;
     int32_t batch;
     int32_t table_major;   // gradient layout: 0 = [B, sumD] rows, 1 = one [B, D_t] block per table
+    // dense hot rows (runs longer than dense_thr): queued per table by the update kernel, summed by dense_rows_kernel
+    int32_t dense_thr;     // >= kDenseMinRun; INT32_MAX switches the dense path off
+    int32_t dense_slices;  // ceil(batch / kDenseSlice): partial rows per dense run
+    const int32_t* tstart; // [T+1] first sorted position of every table
+    uint32_t* dense_cnt;   // [T] dense runs queued per table (zero between updates)
+    uint32_t* dense_list;  // table t's queue starts at entry tstart[t] / dense_thr + t
+    uint32_t* dense_dirty; // [T] set by dense_rows_kernel when a table's gradient block holds Inf / NaN
     OptParams opt;
 };
 
@@ -1189,6 +1220,7 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     constexpr int kWaves = kBwdThreads / kWave;
     constexpr int kSegCap = 3 * kWave;             // >= kChunk + 1
     constexpr int kValCap = kChunk + kLongRun;     // a run owned by the chunk ends within this window
+    static_assert(kFwdUnroll == 4, "the forward adds its four accumulators pairwise");
     static_assert(kChunk + 1 <= kSegCap && kChunk == 2 * kWave, "staging loops assume a 128-position chunk");
     __shared__ int32_t s_seg_all[kWaves][kSegCap];
     __shared__ uint32_t s_key_all[kWaves][kChunk];
@@ -1209,6 +1241,13 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     const int ue = a.chunk_first_run[k + 1];
     const int U = (int)a.counters->num_unique;
     const int nruns = ue - ub;  // runs that start in [q0, q1): at most kChunk
+    if (nruns == 0) {
+        // the chunk lies inside one run; a dense run leaves nothing to do here (dense_rows_kernel sums it)
+        const int sd = a.seg_offsets[ub - 1];
+        const int ed = a.seg_offsets[ub];
+        if (ed - sd > a.dense_thr)
+            return;
+    }
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     const int32_t* __restrict__ vals = a.sorted_vals;
     int64_t sumD = a.sumD;   // distance between the gradient rows of consecutive bags (D_t when table-major)
@@ -1271,7 +1310,7 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         const int u0 = ub - 1;
         const int s0 = a.seg_offsets[u0];
         const int e0 = a.seg_offsets[u0 + 1];
-        if (e0 - s0 > kLongRun) {
+        if (e0 - s0 > kLongRun && e0 - s0 <= a.dense_thr) {
             seek_table(a.unique_keys[u0]);
             const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
             sumD = a.table_major ? m.dim : a.sumD;
@@ -1299,6 +1338,17 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
             const int64_t rel = (int64_t)(key0 - m.rbase) * D;
             WT* wrow = wtab + rel;
             const bool is_long = len0 > kLongRun;
+            if (len0 > a.dense_thr) {
+                // dense run: queued for dense_rows_kernel (per table) and for the fix-up, nothing is gathered here
+                if (lane == 0) {
+                    const uint32_t dslot = atomicAdd(&a.dense_cnt[t], 1u);
+                    a.dense_list[a.tstart[t] / a.dense_thr + t + (int)dslot] = (uint32_t)(ub + r);
+                    const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
+                    a.long_list[slot] = (uint32_t)(ub + r) | 0x80000000u;
+                }
+                r += 1;
+                continue;
+            }
             typename IO::Vec wvv[2];
             OptRow<OPT> st;
             if (!is_long) {
@@ -1349,10 +1399,365 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     }
 }
 
+// ---------------------------------------------------------------- dense hot rows
+//
+// Under a skewed index distribution a few rows per table are looked up by a large share of the bags
+// (Section 5.1 aggregates all of their gradients before the one optimizer step).  Gathering one gradient
+// row per lookup re-reads the table's [B, D_t] gradient block once per such row.  For a run longer than
+// the call's dense threshold (about one lookup per 12 bags) the sum is formed the other way round:
+//     G[r, :] = sum_b count[r, b] * grad[b, :]
+// with count[r, b] = how often bag b looks row r up.  kDenseRows runs of one table form a group and share
+// ONE pass over the gradient block; a work unit is (group, slice of kDenseSlice bags) and writes one fp32
+// partial row per run into the slots of the chunks that run covers completely (the update kernel leaves
+// them unused); the fix-up kernel adds a run's partial rows in slice order and applies the single step.
+// Counts are exact integers built with LDS integer atomics from the run's sorted payloads; the float sum of
+// a (run, slice) has a fixed order that does not depend on which other runs share the group, so results
+// are bit-identical run to run.  A bag with a non-finite gradient must only reach the rows it looks up:
+// such a bag takes a select-based path instead of multiplying by a zero count.
+
+struct DenseGroup {      // 32 bytes
+    int32_t t;           // table
+    int32_t first;       // index of the group's first run in the compact run list
+    int32_t nrows;       // runs in the group (1..kDenseRows)
+    int32_t gbase;       // first group of the table
+    int32_t ng;          // groups of the table
+    int32_t pad[3];
+};
+
+struct DenseArgs {
+    BwdArgs b;
+    const uint32_t* drun;       // compact list of dense runs (run index u), grouped by table
+    const DenseGroup* dgroup;
+    int32_t* dbounds;           // [run][nsub + 1] first sorted position of the run whose bag is >= c * kDenseSub
+    int32_t nsub;               // ceil(batch / kDenseSub)
+};
+
+// one workgroup: per-table queues -> compact run list + groups; clears the per-table counters
+__global__ __launch_bounds__(256) void dense_plan_kernel(BwdArgs a, uint32_t* __restrict__ drun,
+                                                         DenseGroup* __restrict__ dgroup)
+{
+    __shared__ uint32_t s_wave[4];
+    __shared__ uint32_t s_c[256], s_rfirst[256], s_gfirst[256];
+    uint32_t carry_r = 0, carry_g = 0;
+    for (int base = 0; base < a.T; base += 256) {
+        const int t = base + threadIdx.x;
+        const uint32_t c = t < a.T ? a.dense_cnt[t] : 0u;
+        const uint32_t rpg = (uint32_t)kDenseRows;
+        const uint32_t g = (c + rpg - 1) / rpg;
+        if (t < a.T)
+            a.dense_dirty[t] = 0;
+        uint32_t tot_r, tot_g;
+        const uint32_t ex_r = block_exclusive_scan_256(c, s_wave, tot_r);
+        const uint32_t ex_g = block_exclusive_scan_256(g, s_wave, tot_g);
+        s_c[threadIdx.x] = c;
+        s_rfirst[threadIdx.x] = carry_r + ex_r;
+        s_gfirst[threadIdx.x] = carry_g + ex_g;
+        if (c > 0)
+            a.dense_cnt[t] = 0;
+        __syncthreads();
+        // the whole workgroup copies one table's queue after the other (a queue can be long when the batch is small)
+        const int nt = min(256, a.T - base);
+        for (int tt = 0; tt < nt; ++tt) {
+            const uint32_t ct = s_c[tt];
+            if (ct == 0)
+                continue;
+            const uint32_t rfirst = s_rfirst[tt], gfirst = s_gfirst[tt];
+            const uint32_t rpg = (uint32_t)kDenseRows;
+            const uint32_t gt = (ct + rpg - 1) / rpg;
+            const uint32_t* q = a.dense_list + (a.tstart[base + tt] / a.dense_thr + base + tt);
+            for (uint32_t i = threadIdx.x; i < ct; i += 256)
+                drun[rfirst + i] = q[i];
+            for (uint32_t gi = threadIdx.x; gi < gt; gi += 256) {
+                DenseGroup d;
+                d.t = base + tt;
+                d.first = (int32_t)(rfirst + gi * rpg);
+                d.nrows = (int32_t)min(rpg, ct - gi * rpg);
+                d.gbase = (int32_t)gfirst;
+                d.ng = (int32_t)gt;
+                d.pad[0] = d.pad[1] = d.pad[2] = 0;
+                dgroup[gfirst + gi] = d;
+            }
+        }
+        __syncthreads();
+        carry_r += tot_r;
+        carry_g += tot_g;
+    }
+    if (threadIdx.x == 0) {
+        a.counters->dense_runs = carry_r;
+        a.counters->dense_groups = carry_g;
+    }
+}
+
+// one wavefront per dense run: where the run's payloads (ascending bags) cross every multiple of kDenseSub
+__global__ __launch_bounds__(256) void dense_bounds_kernel(DenseArgs d)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave_global = uniform(blockIdx.x * 4 + (threadIdx.x >> 6));
+    const int wave_total = gridDim.x * 4;
+    const int nruns = (int)d.b.counters->dense_runs;
+    const int nb = d.nsub + 1;
+    const int32_t* __restrict__ vals = d.b.sorted_vals;
+    for (int i = wave_global; i < nruns; i += wave_total) {
+        const int u = (int)d.drun[i];
+        const int s = d.b.seg_offsets[u];
+        const int e = d.b.seg_offsets[u + 1];
+        for (int c = lane; c < nb; c += kWave) {
+            const int target = c * kDenseSub;
+            int lo = s, hi = e;              // first p in [s, e) with vals[p] >= target
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (vals[mid] < target)
+                    lo = mid + 1;
+                else
+                    hi = mid;
+            }
+            d.dbounds[(int64_t)i * nb + c] = c == d.nsub ? e : lo;
+        }
+    }
+}
+
+template <typename GT>
+__device__ __forceinline__ void grad_unpack4(const typename GradIO<GT>::Vec v, float (&g)[4])
+{
+    g[0] = g[1] = g[2] = g[3] = 0.f;
+    GradIO<GT>::add(g, v);   // 0 + x is x for every x that is not -0 (which sums like +0)
+}
+
+typedef float mfma_f4 __attribute__((ext_vector_type(4)));
+
+// One (group, slice) unit for a table of D columns: RT tiles of 16 runs, CL loads of 64 columns per bag.
+// The contraction runs on the matrix cores in fp32 (v_mfma_f32_16x16x4_f32: 16 runs x 16 columns x 4 bags;
+// operand A = counts, lane l holds run l%16 of bag l/16; operand B = gradient, lane l holds one column of
+// bag l/16; a lane's float4 gradient load covers columns 4*(l%16)..+3, so tile q of a load takes component
+// q and holds columns 4*(l%16)+q; result tile: lane l holds runs 4*(l/16)+i, i = 0..3).  Counts are exact
+// small integers, products and sums are fp32: the same arithmetic as adding the gradient row count times.
+template <typename GT, int RT, int CL>
+__device__ __forceinline__ void dense_unit(const DenseArgs& d, const DenseGroup& grp, const TableMeta& m, int j,
+                                           float* __restrict__ s_cnt, int32_t* __restrict__ s_p0,
+                                           int32_t* __restrict__ s_pre, int32_t* __restrict__ s_slot,
+                                           bool& nonfinite)
+{
+    using GIO = GradIO<GT>;
+    constexpr int kWaves = kDenseThreads / kWave;
+    constexpr int kBagsPerWave = kDenseSub / kWaves;          // 64 bags = 16 steps of 4
+    constexpr int kSteps = kBagsPerWave / 4;
+    constexpr int kUnroll = CL == 1 ? 4 : 2;                  // gradient loads in flight: 4 x 16 bytes per lane
+    const BwdArgs& a = d.b;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = threadIdx.x >> 6;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int D = m.dim;
+    const int nb = d.nsub + 1;
+    const int64_t stride = a.table_major ? D : a.sumD;
+    const GT* __restrict__ grad_out = static_cast<const GT*>(a.grad_out);
+    const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
+    const GT* zero_row = reinterpret_cast<const GT*>(a.zero_row);
+    const int32_t* __restrict__ vals = a.sorted_vals;
+    uint32_t* s_cnt_u = reinterpret_cast<uint32_t*>(s_cnt);
+
+    for (int cbase = 0; cbase < D; cbase += CL * 64) {
+        int coff[CL];
+        bool cvalid[CL];
+#pragma unroll
+        for (int cl = 0; cl < CL; ++cl) {
+            const int c0 = cbase + cl * 64 + 4 * l16;
+            cvalid[cl] = c0 < D;
+            coff[cl] = min(c0, D - 4);
+        }
+        mfma_f4 acc[RT][CL][4];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int cl = 0; cl < CL; ++cl)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc[rt][cl][q] = mfma_f4{0.f, 0.f, 0.f, 0.f};
+
+        for (int sb = 0; sb < kDenseSlice / kDenseSub; ++sb) {
+            const int c = j * (kDenseSlice / kDenseSub) + sb;
+            const int sb_lo = c * kDenseSub;
+            if (sb_lo >= a.batch)
+                break;
+            const int sb_n = min(kDenseSub, a.batch - sb_lo);
+            // ---- count table of this piece: zero, one LDS integer atomic per lookup, then to float in place
+            __syncthreads();
+            for (int i = threadIdx.x; i < kDenseSub * kDenseRows / 4; i += kDenseThreads)
+                reinterpret_cast<uint4*>(s_cnt_u)[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (threadIdx.x < kDenseRows) {
+                int p0 = 0, cntr = 0;
+                if ((int)threadIdx.x < grp.nrows) {
+                    const int64_t bi = (int64_t)(grp.first + threadIdx.x) * nb + c;
+                    p0 = d.dbounds[bi];
+                    cntr = d.dbounds[bi + 1] - p0;
+                }
+                s_p0[threadIdx.x] = p0;
+                int incl = cntr;   // inclusive prefix over the group's runs inside the first wavefront
+#pragma unroll
+                for (int o = 1; o < kDenseRows; o <<= 1) {
+                    const int up = __shfl_up(incl, o);
+                    if ((int)threadIdx.x >= o)
+                        incl += up;
+                }
+                s_pre[threadIdx.x + 1] = incl;
+                if (threadIdx.x == 0)
+                    s_pre[0] = 0;
+            }
+            __syncthreads();
+            const int tot = s_pre[kDenseRows];
+            for (int f0 = 0; f0 < tot; f0 += kDenseThreads * 4) {
+                int rr[4], bb[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {       // all four loads are issued before the first atomic
+                    const int f = f0 + x * kDenseThreads + threadIdx.x;
+                    int lo = 0, hi = kDenseRows;    // last r with s_pre[r] <= f
+#pragma unroll
+                    for (int st = 0; st < 5; ++st) {
+                        const int mid = (lo + hi) >> 1;
+                        if (s_pre[mid] <= f)
+                            lo = mid;
+                        else
+                            hi = mid;
+                    }
+                    rr[x] = f < tot ? lo : -1;
+                    bb[x] = f < tot ? vals[s_p0[lo] + (f - s_pre[lo])] : 0;
+                }
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if (rr[x] >= 0)
+                        atomicAdd(&s_cnt_u[(bb[x] - sb_lo) * kDenseRows + rr[x]], 1u);
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < kDenseSub * kDenseRows / 4; i += kDenseThreads) {
+                const uint4 v = reinterpret_cast<const uint4*>(s_cnt_u)[i];
+                reinterpret_cast<float4*>(s_cnt)[i] = make_float4((float)v.x, (float)v.y, (float)v.z, (float)v.w);
+            }
+            __syncthreads();
+            // ---- counts x gradient rows on the matrix cores; a wavefront takes kBagsPerWave consecutive bags
+            const int wbase = wv * kBagsPerWave;
+            for (int s0 = 0; s0 < kSteps && wbase + s0 * 4 < sb_n; s0 += kUnroll) {
+                typename GIO::Vec raw[kUnroll][CL];
+                int bl[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int x = wbase + (s0 + u) * 4 + kq;
+                    const bool ok = x < sb_n && s0 + u < kSteps;
+                    bl[u] = ok ? x : 0;
+                    const GT* rp = ok ? gb + (int64_t)(sb_lo + x) * stride : zero_row;
+                    const int zfix = ok ? 0 : 1;    // the row of zeros has no column offset beyond its 4 KiB
+#pragma unroll
+                    for (int cl = 0; cl < CL; ++cl)
+                        raw[u][cl] = GIO::ldv(rp + (zfix ? 0 : coff[cl]));
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    float av[RT];
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        av[rt] = s_cnt[bl[u] * kDenseRows + rt * 16 + l16];
+#pragma unroll
+                    for (int cl = 0; cl < CL; ++cl) {
+                        float g[4];
+                        grad_unpack4<GT>(raw[u][cl], g);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            // 0 x Inf would reach runs the bag does not look up: non-finite values are taken
+                            // out here and the table is flagged, its dense runs are then summed by gathering
+                            const bool fin = (__float_as_uint(g[q]) & 0x7f800000u) != 0x7f800000u;
+                            nonfinite = nonfinite || !fin;
+                            const float gq = fin ? g[q] : 0.f;
+#pragma unroll
+                            for (int rt = 0; rt < RT; ++rt)
+                                acc[rt][cl][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rt], gq, acc[rt][cl][q], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+        // ---- wavefronts of the workgroup, in wavefront order, one tile of 16 runs at a time through LDS
+        if (cbase == 0 && threadIdx.x < kDenseRows) {
+            int slot = 0;
+            if ((int)threadIdx.x < grp.nrows) {
+                const int u = (int)d.drun[grp.first + threadIdx.x];
+                slot = (a.seg_offsets[u] / kChunk + 1) * 2 + j;
+            }
+            s_slot[threadIdx.x] = slot;
+        }
+        constexpr int kCH = CL < 2 ? CL : 2;                // 64-column loads per pass through LDS
+        constexpr int kW = kCH * 64;                        // columns per pass
+        float* s_red = s_cnt;                               // [kWaves][16][kW] floats <= 32 KiB
+        for (int rt = 0; rt < RT; ++rt) {
+            for (int ch = 0; ch < CL; ch += kCH) {
+                __syncthreads();
+#pragma unroll
+                for (int cl = 0; cl < CL; ++cl) {
+                    if (cl >= ch && cl < ch + kCH) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            *reinterpret_cast<float4*>(&s_red[(wv * 16 + 4 * kq + i) * kW + (cl - ch) * 64 + 4 * l16]) =
+                                make_float4(acc[rt][cl][0][i], acc[rt][cl][1][i], acc[rt][cl][2][i], acc[rt][cl][3][i]);
+                    }
+                }
+                __syncthreads();
+                for (int idx = threadIdx.x; idx < 16 * (kW / 4); idx += kDenseThreads) {
+                    const int r = idx / (kW / 4);
+                    const int c4 = (idx - r * (kW / 4)) * 4;
+                    const int row = rt * 16 + r;
+                    const int col = cbase + ch * 64 + c4;
+                    if (row < grp.nrows && col < D) {
+                        float4 sum = *reinterpret_cast<const float4*>(&s_red[r * kW + c4]);
+#pragma unroll
+                        for (int w2 = 1; w2 < kWaves; ++w2) {
+                            const float4 v = *reinterpret_cast<const float4*>(&s_red[(w2 * 16 + r) * kW + c4]);
+                            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                        }
+                        *reinterpret_cast<float4*>(a.partials + (int64_t)s_slot[row] * a.dpad + col) = sum;
+                    }
+                }
+            }
+        }
+        (void)cvalid;
+    }
+}
+
+template <typename GT>
+__global__ __launch_bounds__(kDenseThreads, 4) void dense_rows_kernel(DenseArgs d)
+{
+    __shared__ __align__(16) float s_cnt[kDenseSub * kDenseRows];   // 32 KiB; reused for the cross-wave sums
+    __shared__ int32_t s_p0[kDenseRows], s_pre[kDenseRows + 1], s_slot[kDenseRows];
+    const BwdArgs& a = d.b;
+    const int ngroups = (int)a.counters->dense_groups;
+    const int nslices = a.dense_slices;
+    const int total = ngroups * nslices;
+    // Work units in an order that keeps the groups of one (table, slice) next to each other, and the
+    // workgroups that share an L2 (every 8th one) on neighbouring units: they then read the same piece of
+    // the gradient block at about the same time.
+    const int xcd = blockIdx.x & 7, nper = gridDim.x >> 3, within = blockIdx.x >> 3;
+    const int per_xcd = (total + 7) / 8;
+    for (int w = within; w < per_xcd; w += nper) {
+        const int unit = xcd * per_xcd + w;
+        if (unit >= total)
+            break;
+        // unit -> (group, slice): the units of table t are [gbase * nslices, (gbase + ng) * nslices), slice-major
+        const DenseGroup any = d.dgroup[unit / nslices];
+        const int local = unit - any.gbase * nslices;
+        const int j = local / any.ng;
+        const DenseGroup grp = d.dgroup[any.gbase + (local - j * any.ng)];
+        const TableMeta m = a.meta[grp.t];
+        bool nonfinite = false;
+        // 128 columns per pass (64 for narrow tables); wider rows take further passes over the same bags
+        if (m.dim > 64)
+            dense_unit<GT, 2, 2>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, nonfinite);
+        else
+            dense_unit<GT, 2, 1>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, nonfinite);
+        if (__ballot(nonfinite) != 0ull && (threadIdx.x & (kWave - 1)) == 0)
+            atomicOr(&a.dense_dirty[grp.t], 1u);
+    }
+}
+
 // One wavefront per queued long run: adds the per-chunk partial rows in chunk order (first the
 // piece written by the chunk where the run starts, then one piece per following chunk) and applies
 // the run's single AdaGrad step.
-template <typename WT, int OPT>
+template <typename WT, typename GT, int OPT>
 __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
 {
     using IO = RowIO<WT, 4>;
@@ -1363,7 +1768,9 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     float acc[2][4];
     for (int i = wave_global; i < cnt; i += wave_total) {
-        const int u = (int)a.long_list[i];
+        const uint32_t entry = a.long_list[i];
+        const bool dense = (entry & 0x80000000u) != 0u;
+        const int u = (int)(entry & 0x7fffffffu);
         const int s = a.seg_offsets[u];
         const int e = a.seg_offsets[u + 1];
         const uint32_t key = a.unique_keys[u];
@@ -1381,8 +1788,22 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
         wvv[1] = IO::ldv(wrow + c.e1);
         OptRow<OPT> st;
         st.load(a.opt, key, wel, c);
-        wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + cc) * 2 + (cc == 0 ? 1 : 0)) * dpad; },
-                               0, k1 - k0 + 1, a.zero_row, c, acc);
+        if (dense && a.dense_dirty[t] != 0u) {
+            // the table's gradient block holds Inf / NaN, which the dense sums leave out: this run is
+            // summed the plain way, one gathered gradient row per lookup (a rare, slow path)
+            const GT* gb = a.table_major ? static_cast<const GT*>(a.grad_out) + (int64_t)a.batch * m.col
+                                         : static_cast<const GT*>(a.grad_out) + m.col;
+            const int64_t gstride = a.table_major ? m.dim : a.sumD;
+            const int32_t* __restrict__ vals = a.sorted_vals;
+            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)vals[i] * gstride; }, s, e, a.zero_row, c, acc);
+        } else if (dense) {
+            // one partial row per slice of bags, kept in the slots of the chunks the run covers completely
+            wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + 1) * 2 + cc) * dpad; }, 0,
+                                   a.dense_slices, a.zero_row, c, acc);
+        } else {
+            wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + cc) * 2 + (cc == 0 ? 1 : 0)) * dpad; },
+                                   0, k1 - k0 + 1, a.zero_row, c, acc);
+        }
         optimizer_epilogue<WT, OPT>(wrow, wvv, acc, m.dim, c, c.grp == 0, a.opt, key, wel, st);
     }
     // Leave the queue empty for the next update launch.  Every wavefront read the count before its

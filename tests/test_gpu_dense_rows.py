@@ -1,0 +1,136 @@
+"""GPU parity of the dense-hot-row path of the fused backward: runs longer than the call's threshold
+(max(1024, batch / 12) lookups) are summed as count matrix x gradient block, 16 runs of a table per group,
+1024 bags per partial row, instead of one gathered gradient row per lookup.  The cases put many such runs
+into one table (several groups), span several bag slices with a ragged last one, use the narrowest and the
+widest rows, both layouts and all gradient types, a batch of three bags with hundreds of copies of a row per
+bag, and a gradient with Inf / NaN entries (which may only reach the rows their bag looks up).
+Everything is compared with the CPU oracle element by element; integer artefacts bit-exactly."""
+import numpy as np
+import pytest
+import torch
+
+import tbe_testlib as tl
+from oracle import tbe_oracle as orc
+from paper_2104_05158_amd import tbe
+from paper_2104_05158_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # name: (rows, dims, batch, pooling, index distribution, zipf exponent)
+    "two_groups_three_slices": ([40, 3000, 100000], [128, 64, 256], 2500, [60.0, 30.0, 20.0], "zipf", 1.3),
+    "narrow_and_widest_rows": ([30, 25, 60], [512, 4, 260], 1100, [40.0, 40.0, 30.0], "uniform", 0.0),
+    "three_bags_hundreds_of_copies": ([5, 3], [64, 8], 3, [2000.0, 1500.0], "uniform", 0.0),
+    "every_row_dense": ([20], [128], 5000, [10.0], "uniform", 0.0),
+    "threshold_follows_batch": ([200, 50], [32, 96], 16384, [8.0, 3.0], "zipf", 1.2),
+    "many_dense_runs_small_batch": ([70], [16], 64, [2500.0], "uniform", 0.0),
+}
+
+
+def _spec(name, dtype):
+    rows, dims, B, pooling, dist, s = CASES[name]
+    return wl.custom(rows, dims, dtype, B, pooling, index_dist=dist, zipf_s=s or 1.05, name=name)
+
+
+def _dense_runs(spec, idx, off):
+    B = spec.batch
+    nslices = -(-B // 1024)
+    thr = max(1024, B // 12, 128 * ((nslices + 1) // 2 + 3))
+    n = 0
+    for t in range(spec.T):
+        n += int((np.bincount(idx[off[t * B]:off[(t + 1) * B]], minlength=1) > thr).sum())
+    return n, thr
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_dense_rows_parity(gpu_device, case, dtype, layout):
+    spec = _spec(case, dtype)
+    b = wl.make_batch(spec, "cpu", seed=11)
+    idx, off = b.indices.numpy(), b.offsets.numpy()
+    nd, thr = _dense_runs(spec, idx, off)
+    assert nd > 0, "the case must contain runs beyond the dense threshold"
+    print(f"{case}: N={b.num_indices} dense runs {nd} (threshold {thr}) dtype={dtype} layout={layout}", flush=True)
+    w = wl.make_weights(spec, "cpu", seed=12).numpy()
+    g = wl.make_grad(spec, "cpu", seed=13).numpy()
+    rng = np.random.default_rng(3)
+    m0 = rng.uniform(0, 1, spec.total_rows).astype(np.float32)
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, lr=0.02, m0=m0, what=case, layout=layout)
+
+
+@pytest.mark.parametrize("grad_dtype", [tbe.TBE_DTYPE_FP16, tbe.TBE_DTYPE_BF16])
+@pytest.mark.parametrize("case", ["two_groups_three_slices", "narrow_and_widest_rows"])
+def test_dense_rows_with_16bit_gradients_table_major(gpu_device, case, grad_dtype):
+    dev = gpu_device
+    spec = _spec(case, 1)
+    b = wl.make_batch(spec, "cpu", seed=21)
+    idx, off = b.indices.numpy(), b.offsets.numpy()
+    N, B = b.num_indices, spec.batch
+    w0 = wl.make_weights(spec, "cpu", seed=22).numpy()
+    m0 = np.zeros(spec.total_rows, np.float32)
+    g_t = torch.from_numpy(wl.make_grad(spec, "cpu", seed=23).numpy()).to(tbe._TORCH_DTYPE[grad_dtype])
+    g32 = g_t.float().numpy()            # the oracle gets exactly the values the library reads
+    ref = tl.oracle_step(spec, idx, off, w0, m0, g32, 0.01, 1e-8)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, 1, B, N, device=dev,
+                                       weights=torch.from_numpy(w0.copy()).to(dev), grad_dtype=grad_dtype,
+                                       layout=tbe.TBE_LAYOUT_TABLE_MAJOR)
+    d_grad = torch.from_numpy(tl.to_table_major(g32, spec.dims)).to(dev).to(tbe._TORCH_DTYPE[grad_dtype])
+    op.backward_rowwise_adagrad(b.indices.to(dev), b.offsets.to(dev), B, d_grad, 0.01, 1e-8, num_indices=N)
+    tl.assert_artifacts_equal(op.artifacts(), ref["art"], case)
+    tl.assert_update_close(spec, ref, w0, m0, op.weights.cpu().numpy(), op.state.cpu().numpy(), 0.01, 1e-8, case)
+    op.close()
+
+
+def test_dense_rows_other_optimizers(gpu_device):
+    import test_gpu_optimizers as tgo
+
+    for optimizer in (tbe.TBE_OPT_ADAGRAD, tbe.TBE_OPT_ADAM):
+        tgo._run(_spec("two_groups_three_slices", 1), optimizer, tbe.TBE_DTYPE_FP32, gpu_device, steps=2, seed=40)
+
+
+def test_non_finite_gradient_reaches_only_the_rows_its_bag_looks_up(gpu_device):
+    """Bag 7 of table 0 carries an Inf and a NaN gradient entry.  Rows (dense or not) that bag 7 does not look
+    up must come out exactly as with a finite gradient; rows it does look up must show the same non-finite
+    pattern as the oracle."""
+    dev = gpu_device
+    spec = wl.custom([24, 500], [128, 64], 0, 1500, [12.0, 6.0], index_dist="zipf", zipf_s=1.2, name="nonfinite")
+    b = wl.make_batch(spec, "cpu", seed=31)
+    idx, off = b.indices.numpy().copy(), b.offsets.numpy()
+    B, N = spec.batch, b.num_indices
+    # make sure some dense row is NOT in bag 7: the hottest row is taken out of it (redirected to the second hottest)
+    seg = slice(int(off[7]), int(off[8]))
+    order = np.argsort(np.bincount(idx[off[0]:off[B]], minlength=24))
+    h0, h1 = int(order[-1]), int(order[-2])
+    idx[seg] = np.where(idx[seg] == h0, h1, idx[seg])
+    nd, thr = _dense_runs(spec, idx, off)
+    counts0 = np.bincount(idx[off[0]:off[B]], minlength=24)
+    assert counts0[h0] > thr and counts0[h1] > thr
+    w0 = wl.make_weights(spec, "cpu", seed=32).numpy()
+    m0 = np.zeros(spec.total_rows, np.float32)
+    g = wl.make_grad(spec, "cpu", seed=33).numpy()
+    g[7, 5] = np.inf
+    g[7, 70] = np.nan
+    with np.errstate(all="ignore"):
+        ref = tl.oracle_step(spec, idx, off, w0, m0, g, 0.01, 1e-8)
+    op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, 0, B, N, device=dev,
+                                       weights=torch.from_numpy(w0.copy()).to(dev))
+    op.backward_rowwise_adagrad(torch.from_numpy(idx).to(dev), b.offsets.to(dev), B, torch.from_numpy(g).to(dev),
+                                0.01, 1e-8, num_indices=N)
+    torch.cuda.synchronize()
+    gw, gm = op.weights.cpu().numpy(), op.state.cpu().numpy()
+    in_bag7 = np.unique(idx[seg])
+    H0, D0 = 24, 128
+    W_ref, W_gpu = ref["w1"][:H0 * D0].reshape(H0, D0), gw[:H0 * D0].reshape(H0, D0)
+    clean = np.setdiff1d(np.arange(H0), in_bag7)
+    assert h0 in clean
+    assert np.isfinite(W_gpu[clean]).all() and np.isfinite(gm[clean]).all(), "a row outside the bad bag was poisoned"
+    np.testing.assert_allclose(W_gpu[clean], W_ref[clean], rtol=1e-4, atol=1e-6)
+    # rows that do look the bad bag up: same non-finite pattern, finite elements agree
+    assert np.array_equal(np.isnan(W_gpu[in_bag7]), np.isnan(W_ref[in_bag7]))
+    assert np.array_equal(np.isnan(gm[in_bag7]) | np.isinf(gm[in_bag7]), ~np.isfinite(ref["m1"][in_bag7]))
+    fin = np.isfinite(W_ref[in_bag7])
+    np.testing.assert_allclose(W_gpu[in_bag7][fin], W_ref[in_bag7][fin], rtol=1e-4, atol=1e-6)
+    # the other table is untouched by all this
+    np.testing.assert_allclose(gw[H0 * D0:], ref["w1"][H0 * D0:], rtol=1e-4, atol=1e-6)
+    op.close()
