@@ -41,7 +41,8 @@ const char* const kSlotNames[SLOT_COUNT] = {"forward",       "sort_plan",  "radi
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
-constexpr int kDenseGrid = 1024;   // persistent workgroups of dense_rows_kernel: 4 per CU, a multiple of 8
+constexpr int kDenseGrid = 1024;
+constexpr int kDenseBagsPerLookup = 8;   // persistent workgroups of dense_rows_kernel: 4 per CU, a multiple of 8
 
 inline int pow2ceil_log2(int x)
 {
@@ -157,14 +158,15 @@ tbe_status_t hip_fail(tbe_s* h, hipError_t e, const char* what)
             return hip_fail((h), e_, what);        \
     } while (0)
 
-// Dense hot rows: the run-length threshold for a call with `batch` bags per table.  About one lookup per
-// 12 bags is where summing counts x gradient block becomes cheaper than one gathered row per lookup; the
-// third term keeps the partial rows of a dense run (one per kDenseSlice bags) inside the slots of the
-// chunks that run covers completely (two per chunk).
+// Dense hot rows: the run-length threshold for a call with `batch` bags per table.  One lookup per
+// kDenseBagsPerLookup bags is where summing counts x gradient block pays (measured on configurations 2-4:
+// with 8 a table's first group of 32 runs saves twice what it costs, a second group costs more than it
+// saves); the third term keeps the partial rows of a dense run (one per kDenseSlice bags) inside the slots
+// of the chunks that run covers completely (two per chunk).
 int dense_threshold(int64_t batch)
 {
     const int64_t nslices = ceil_div(std::max<int64_t>(batch, 1), kDenseSlice);
-    return (int)std::max<int64_t>({kDenseMinRun, batch / 12, (int64_t)kChunk * ((nslices + 1) / 2 + 3)});
+    return (int)std::max<int64_t>({kDenseMinRun, batch / kDenseBagsPerLookup, (int64_t)kChunk * ((nslices + 1) / 2 + 3)});
 }
 
 // entries of the bounds table a call with n lookups and `batch` bags per table can need
@@ -173,7 +175,7 @@ int64_t dense_bounds_entries(int64_t n, int64_t batch, int T)
     if (batch <= 0)
         return 0;
     const int64_t runs = n / dense_threshold(batch) + 1;
-    return runs * (ceil_div(batch, kDenseSub) + 1);
+    return runs * (ceil_div(batch, kDenseSlice) + 1);
 }
 
 void plan_workspace(tbe_s* h)
@@ -213,7 +215,7 @@ void plan_workspace(tbe_s* h)
     h->off_partials = take(4 * (size_t)chunks * 2 * (size_t)dpad);
     h->off_long_list = take(4 * (size_t)(nmax / kLongRun + 2));
     // dense hot rows: per-table queues, compact run list, groups, and the runs' positions at every
-    // kDenseSub-th bag.  The threshold is never below kDenseMinRun, which bounds the number of dense runs.
+    // kDenseSlice-th bag.  The threshold is never below kDenseMinRun, which bounds the number of dense runs.
     const int64_t dense_runs_max = nmax / kDenseMinRun + h->T + 2;
     h->off_dense_cnt = take(4 * (size_t)h->T);
     h->off_dense_dirty = take(4 * (size_t)h->T);
@@ -621,7 +623,7 @@ static void launch_update(const BwdArgs& a, dim3 grid, dim3 grid_fix, hipStream_
         d.drun = h->ws<uint32_t>(h->off_drun);
         d.dgroup = h->ws<DenseGroup>(h->off_dgroup);
         d.dbounds = h->ws<int32_t>(h->off_dbounds);
-        d.nsub = (int32_t)ceil_div(a.batch, kDenseSub);
+        d.nsub = (int32_t)ceil_div(a.batch, kDenseSlice);
         hipLaunchKernelGGL(dense_plan_kernel, dim3(1), dim3(256), 0, st, a, h->ws<uint32_t>(h->off_drun),
                            h->ws<DenseGroup>(h->off_dgroup));
         hipLaunchKernelGGL(dense_bounds_kernel, dim3(512), dim3(256), 0, st, d);

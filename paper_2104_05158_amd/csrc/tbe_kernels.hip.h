@@ -40,8 +40,7 @@ constexpr int kShortRun = 4;              // runs up to this length are handled 
 constexpr int kMaxDim = 512;
 // dense hot rows: runs longer than the call's dense threshold are summed as (count matrix) x (gradient block)
 constexpr int kDenseRows = 32;            // most runs per group: they share one pass over the table's gradient block
-constexpr int kDenseSub = 256;            // bags per count table held in LDS
-constexpr int kDenseSlice = 4 * kDenseSub;  // bags per work unit = per partial row of a dense run
+constexpr int kDenseSlice = 1024;         // bags per work unit = per count table in LDS = per partial row of a dense run
 constexpr int kDenseThreads = 256;
 constexpr int kDenseMinRun = 1024;        // no run of this length or less is ever treated as dense
 constexpr int kZeroRowBytes = 4096;        // a row of zeros in the workspace (largest row: 512 x fp32 = 2 KiB)
@@ -1404,7 +1403,7 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
 // Under a skewed index distribution a few rows per table are looked up by a large share of the bags
 // (Section 5.1 aggregates all of their gradients before the one optimizer step).  Gathering one gradient
 // row per lookup re-reads the table's [B, D_t] gradient block once per such row.  For a run longer than
-// the call's dense threshold (about one lookup per 12 bags) the sum is formed the other way round:
+// the call's dense threshold (about one lookup per 8 bags) the sum is formed the other way round:
 //     G[r, :] = sum_b count[r, b] * grad[b, :]
 // with count[r, b] = how often bag b looks row r up.  kDenseRows runs of one table form a group and share
 // ONE pass over the gradient block; a work unit is (group, slice of kDenseSlice bags) and writes one fp32
@@ -1428,8 +1427,8 @@ struct DenseArgs {
     BwdArgs b;
     const uint32_t* drun;       // compact list of dense runs (run index u), grouped by table
     const DenseGroup* dgroup;
-    int32_t* dbounds;           // [run][nsub + 1] first sorted position of the run whose bag is >= c * kDenseSub
-    int32_t nsub;               // ceil(batch / kDenseSub)
+    int32_t* dbounds;           // [run][nslices + 1] first sorted position of the run whose bag is >= c * kDenseSlice
+    int32_t nsub;               // number of slices = ceil(batch / kDenseSlice)
 };
 
 // one workgroup: per-table queues -> compact run list + groups; clears the per-table counters
@@ -1488,7 +1487,7 @@ __global__ __launch_bounds__(256) void dense_plan_kernel(BwdArgs a, uint32_t* __
     }
 }
 
-// one wavefront per dense run: where the run's payloads (ascending bags) cross every multiple of kDenseSub
+// one wavefront per dense run: where the run's payloads (ascending bags) cross every multiple of kDenseSlice
 __global__ __launch_bounds__(256) void dense_bounds_kernel(DenseArgs d)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -1502,7 +1501,7 @@ __global__ __launch_bounds__(256) void dense_bounds_kernel(DenseArgs d)
         const int s = d.b.seg_offsets[u];
         const int e = d.b.seg_offsets[u + 1];
         for (int c = lane; c < nb; c += kWave) {
-            const int target = c * kDenseSub;
+            const int target = c * kDenseSlice;
             int lo = s, hi = e;              // first p in [s, e) with vals[p] >= target
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
@@ -1516,54 +1515,125 @@ __global__ __launch_bounds__(256) void dense_bounds_kernel(DenseArgs d)
     }
 }
 
-template <typename GT>
-__device__ __forceinline__ void grad_unpack4(const typename GradIO<GT>::Vec v, float (&g)[4])
-{
-    g[0] = g[1] = g[2] = g[3] = 0.f;
-    GradIO<GT>::add(g, v);   // 0 + x is x for every x that is not -0 (which sums like +0)
-}
-
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
+
+// the four gradient values of one 16-byte (fp32) / 8-byte (16-bit) load as floats
+__device__ __forceinline__ void grad_floats(const float4 v, float (&g)[4]) { g[0] = v.x; g[1] = v.y; g[2] = v.z; g[3] = v.w; }
+__device__ __forceinline__ void grad_floats_half(const uint2 v, float (&g)[4])
+{
+    const float2 x = __half22float2(*reinterpret_cast<const __half2*>(&v.x));
+    const float2 y = __half22float2(*reinterpret_cast<const __half2*>(&v.y));
+    g[0] = x.x; g[1] = x.y; g[2] = y.x; g[3] = y.y;
+}
+__device__ __forceinline__ void grad_floats_bf16(const uint2 v, float (&g)[4])
+{
+    g[0] = __uint_as_float(v.x << 16); g[1] = __uint_as_float(v.x & 0xffff0000u);
+    g[2] = __uint_as_float(v.y << 16); g[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+template <typename GT> struct GradFloats;
+template <> struct GradFloats<float> { __device__ static __forceinline__ void get(const float4 v, float (&g)[4]) { grad_floats(v, g); } };
+template <> struct GradFloats<__half> { __device__ static __forceinline__ void get(const uint2 v, float (&g)[4]) { grad_floats_half(v, g); } };
+template <> struct GradFloats<__hip_bfloat16> { __device__ static __forceinline__ void get(const uint2 v, float (&g)[4]) { grad_floats_bf16(v, g); } };
 
 // One (group, slice) unit for a table of D columns: RT tiles of 16 runs, CL loads of 64 columns per bag.
 // The contraction runs on the matrix cores in fp32 (v_mfma_f32_16x16x4_f32: 16 runs x 16 columns x 4 bags;
 // operand A = counts, lane l holds run l%16 of bag l/16; operand B = gradient, lane l holds one column of
-// bag l/16; a lane's float4 gradient load covers columns 4*(l%16)..+3, so tile q of a load takes component
-// q and holds columns 4*(l%16)+q; result tile: lane l holds runs 4*(l/16)+i, i = 0..3).  Counts are exact
-// small integers, products and sums are fp32: the same arithmetic as adding the gradient row count times.
+// bag l/16; a lane's gradient load covers columns 4*(l%16)..+3, so tile q of a load takes component q and
+// holds columns 4*(l%16)+q; result tile: lane l holds runs 4*(l/16)+i, i = 0..3).  Counts are exact small
+// integers, products and sums are fp32: the same arithmetic as adding the gradient row count times.
+//
+// The count table of the whole slice is one byte per (bag, run), built with LDS integer atomics on the
+// containing words.  A bag that holds one row 256 times or more would overflow its byte, and 0 x Inf / NaN of
+// a bag's gradient would reach runs the bag does not look up: both cases only set the table's dirty flag;
+// the fix-up kernel then ignores the partial rows of that table's dense runs and sums those runs by gathering.
 template <typename GT, int RT, int CL>
 __device__ __forceinline__ void dense_unit(const DenseArgs& d, const DenseGroup& grp, const TableMeta& m, int j,
-                                           float* __restrict__ s_cnt, int32_t* __restrict__ s_p0,
+                                           uint32_t* __restrict__ s_cnt, int32_t* __restrict__ s_p0,
                                            int32_t* __restrict__ s_pre, int32_t* __restrict__ s_slot,
-                                           bool& nonfinite)
+                                           uint32_t& dirty_bits)
 {
     using GIO = GradIO<GT>;
     constexpr int kWaves = kDenseThreads / kWave;
-    constexpr int kBagsPerWave = kDenseSub / kWaves;          // 64 bags = 16 steps of 4
+    constexpr int kBagsPerWave = kDenseSlice / kWaves;        // 256 bags = 64 steps of 4
     constexpr int kSteps = kBagsPerWave / 4;
-    constexpr int kUnroll = CL == 1 ? 4 : 2;                  // gradient loads in flight: 4 x 16 bytes per lane
+    constexpr int kUnroll = CL == 2 ? 2 : 4;                  // steps whose gradient loads are issued together
+    constexpr int kLoads = 8;                                 // payload loads in flight per thread while counting
     const BwdArgs& a = d.b;
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x >> 6;
     const int l16 = lane & 15, kq = lane >> 4;
     const int D = m.dim;
-    const int nb = d.nsub + 1;
+    const int nb = a.dense_slices + 1;
     const int64_t stride = a.table_major ? D : a.sumD;
     const GT* __restrict__ grad_out = static_cast<const GT*>(a.grad_out);
     const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
-    const GT* zero_row = reinterpret_cast<const GT*>(a.zero_row);
     const int32_t* __restrict__ vals = a.sorted_vals;
-    uint32_t* s_cnt_u = reinterpret_cast<uint32_t*>(s_cnt);
+    const uint8_t* s_cnt8 = reinterpret_cast<const uint8_t*>(s_cnt);
+    const int sl_lo = j * kDenseSlice;
+    const int sl_n = min(kDenseSlice, a.batch - sl_lo);       // >= 1
+
+    // ---- count table of the slice
+    __syncthreads();
+    for (int i = threadIdx.x; i < kDenseSlice * kDenseRows / 16; i += kDenseThreads)
+        reinterpret_cast<uint4*>(s_cnt)[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (threadIdx.x < kDenseRows) {
+        int p0 = 0, cntr = 0, slot = 0;
+        if ((int)threadIdx.x < grp.nrows) {
+            const int64_t bi = (int64_t)(grp.first + threadIdx.x) * nb + j;
+            p0 = d.dbounds[bi];
+            cntr = d.dbounds[bi + 1] - p0;
+            const int u = (int)d.drun[grp.first + threadIdx.x];
+            slot = (a.seg_offsets[u] / kChunk + 1) * 2 + j;
+        }
+        s_p0[threadIdx.x] = p0;
+        s_slot[threadIdx.x] = slot;
+        int incl = cntr;   // inclusive prefix over the group's runs inside the first wavefront
+#pragma unroll
+        for (int o = 1; o < kDenseRows; o <<= 1) {
+            const int up = __shfl_up(incl, o);
+            if ((int)threadIdx.x >= o)
+                incl += up;
+        }
+        s_pre[threadIdx.x + 1] = incl;
+        if (threadIdx.x == 0)
+            s_pre[0] = 0;
+    }
+    __syncthreads();
+    const int tot = s_pre[kDenseRows];
+    for (int f0 = 0; f0 < tot; f0 += kDenseThreads * kLoads) {
+        int rr[kLoads], bb[kLoads];
+#pragma unroll
+        for (int x = 0; x < kLoads; ++x) {       // all loads are issued before the first atomic
+            const int f = f0 + x * kDenseThreads + threadIdx.x;
+            int lo = 0, hi = kDenseRows;         // last r with s_pre[r] <= f
+#pragma unroll
+            for (int st = 0; st < 5; ++st) {
+                const int mid = (lo + hi) >> 1;
+                if (s_pre[mid] <= f)
+                    lo = mid;
+                else
+                    hi = mid;
+            }
+            rr[x] = f < tot ? lo : -1;
+            bb[x] = f < tot ? vals[s_p0[lo] + (f - s_pre[lo])] : 0;
+        }
+#pragma unroll
+        for (int x = 0; x < kLoads; ++x) {
+            if (rr[x] >= 0) {
+                const int sh = 8 * (rr[x] & 3);
+                const uint32_t old = atomicAdd(&s_cnt[(bb[x] - sl_lo) * (kDenseRows / 4) + (rr[x] >> 2)], 1u << sh);
+                if (((old >> sh) & 0xffu) == 0xffu)
+                    dirty_bits = 0x7f800000u;    // the byte wrapped around
+            }
+        }
+    }
+    __syncthreads();
 
     for (int cbase = 0; cbase < D; cbase += CL * 64) {
         int coff[CL];
-        bool cvalid[CL];
 #pragma unroll
-        for (int cl = 0; cl < CL; ++cl) {
-            const int c0 = cbase + cl * 64 + 4 * l16;
-            cvalid[cl] = c0 < D;
-            coff[cl] = min(c0, D - 4);
-        }
+        for (int cl = 0; cl < CL; ++cl)
+            coff[cl] = min(cbase + cl * 64 + 4 * l16, D - 4);   // columns past D are computed and dropped
         mfma_f4 acc[RT][CL][4];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
@@ -1573,118 +1643,47 @@ __device__ __forceinline__ void dense_unit(const DenseArgs& d, const DenseGroup&
                 for (int q = 0; q < 4; ++q)
                     acc[rt][cl][q] = mfma_f4{0.f, 0.f, 0.f, 0.f};
 
-        for (int sb = 0; sb < kDenseSlice / kDenseSub; ++sb) {
-            const int c = j * (kDenseSlice / kDenseSub) + sb;
-            const int sb_lo = c * kDenseSub;
-            if (sb_lo >= a.batch)
-                break;
-            const int sb_n = min(kDenseSub, a.batch - sb_lo);
-            // ---- count table of this piece: zero, one LDS integer atomic per lookup, then to float in place
-            __syncthreads();
-            for (int i = threadIdx.x; i < kDenseSub * kDenseRows / 4; i += kDenseThreads)
-                reinterpret_cast<uint4*>(s_cnt_u)[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (threadIdx.x < kDenseRows) {
-                int p0 = 0, cntr = 0;
-                if ((int)threadIdx.x < grp.nrows) {
-                    const int64_t bi = (int64_t)(grp.first + threadIdx.x) * nb + c;
-                    p0 = d.dbounds[bi];
-                    cntr = d.dbounds[bi + 1] - p0;
-                }
-                s_p0[threadIdx.x] = p0;
-                int incl = cntr;   // inclusive prefix over the group's runs inside the first wavefront
-#pragma unroll
-                for (int o = 1; o < kDenseRows; o <<= 1) {
-                    const int up = __shfl_up(incl, o);
-                    if ((int)threadIdx.x >= o)
-                        incl += up;
-                }
-                s_pre[threadIdx.x + 1] = incl;
-                if (threadIdx.x == 0)
-                    s_pre[0] = 0;
-            }
-            __syncthreads();
-            const int tot = s_pre[kDenseRows];
-            for (int f0 = 0; f0 < tot; f0 += kDenseThreads * 4) {
-                int rr[4], bb[4];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {       // all four loads are issued before the first atomic
-                    const int f = f0 + x * kDenseThreads + threadIdx.x;
-                    int lo = 0, hi = kDenseRows;    // last r with s_pre[r] <= f
-#pragma unroll
-                    for (int st = 0; st < 5; ++st) {
-                        const int mid = (lo + hi) >> 1;
-                        if (s_pre[mid] <= f)
-                            lo = mid;
-                        else
-                            hi = mid;
-                    }
-                    rr[x] = f < tot ? lo : -1;
-                    bb[x] = f < tot ? vals[s_p0[lo] + (f - s_pre[lo])] : 0;
-                }
-#pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    if (rr[x] >= 0)
-                        atomicAdd(&s_cnt_u[(bb[x] - sb_lo) * kDenseRows + rr[x]], 1u);
-            }
-            __syncthreads();
-            for (int i = threadIdx.x; i < kDenseSub * kDenseRows / 4; i += kDenseThreads) {
-                const uint4 v = reinterpret_cast<const uint4*>(s_cnt_u)[i];
-                reinterpret_cast<float4*>(s_cnt)[i] = make_float4((float)v.x, (float)v.y, (float)v.z, (float)v.w);
-            }
-            __syncthreads();
-            // ---- counts x gradient rows on the matrix cores; a wavefront takes kBagsPerWave consecutive bags
-            const int wbase = wv * kBagsPerWave;
-            for (int s0 = 0; s0 < kSteps && wbase + s0 * 4 < sb_n; s0 += kUnroll) {
+        // ---- counts x gradient rows on the matrix cores; a wavefront takes kBagsPerWave consecutive bags.
+        // Bags past the end of the batch have all-zero counts; their gradient operand is the batch's last row.
+        const int wbase = wv * kBagsPerWave;
+        const uint8_t* ap = s_cnt8 + (wbase + kq) * kDenseRows + l16;
+        if (wbase < sl_n) {
+            for (int s0 = 0; s0 < kSteps; s0 += kUnroll) {
                 typename GIO::Vec raw[kUnroll][CL];
-                int bl[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
-                    const int x = wbase + (s0 + u) * 4 + kq;
-                    const bool ok = x < sb_n && s0 + u < kSteps;
-                    bl[u] = ok ? x : 0;
-                    const GT* rp = ok ? gb + (int64_t)(sb_lo + x) * stride : zero_row;
-                    const int zfix = ok ? 0 : 1;    // the row of zeros has no column offset beyond its 4 KiB
+                    const int x = min(wbase + (s0 + u) * 4 + kq, sl_n - 1);
+                    const GT* rp = gb + (int64_t)(sl_lo + x) * stride;
 #pragma unroll
                     for (int cl = 0; cl < CL; ++cl)
-                        raw[u][cl] = GIO::ldv(rp + (zfix ? 0 : coff[cl]));
+                        raw[u][cl] = GIO::ldv(rp + coff[cl]);
                 }
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     float av[RT];
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt)
-                        av[rt] = s_cnt[bl[u] * kDenseRows + rt * 16 + l16];
+                        av[rt] = (float)ap[((s0 + u) * 4) * kDenseRows + rt * 16];
 #pragma unroll
                     for (int cl = 0; cl < CL; ++cl) {
                         float g[4];
-                        grad_unpack4<GT>(raw[u][cl], g);
+                        GradFloats<GT>::get(raw[u][cl], g);
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            // 0 x Inf would reach runs the bag does not look up: non-finite values are taken
-                            // out here and the table is flagged, its dense runs are then summed by gathering
-                            const bool fin = (__float_as_uint(g[q]) & 0x7f800000u) != 0x7f800000u;
-                            nonfinite = nonfinite || !fin;
-                            const float gq = fin ? g[q] : 0.f;
+                            dirty_bits = max(dirty_bits, __float_as_uint(g[q]) & 0x7f800000u);   // Inf / NaN: all ones
 #pragma unroll
                             for (int rt = 0; rt < RT; ++rt)
-                                acc[rt][cl][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rt], gq, acc[rt][cl][q], 0, 0, 0);
+                                acc[rt][cl][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[rt], g[q], acc[rt][cl][q], 0, 0, 0);
                         }
                     }
                 }
             }
         }
-        // ---- wavefronts of the workgroup, in wavefront order, one tile of 16 runs at a time through LDS
-        if (cbase == 0 && threadIdx.x < kDenseRows) {
-            int slot = 0;
-            if ((int)threadIdx.x < grp.nrows) {
-                const int u = (int)d.drun[grp.first + threadIdx.x];
-                slot = (a.seg_offsets[u] / kChunk + 1) * 2 + j;
-            }
-            s_slot[threadIdx.x] = slot;
-        }
+        // ---- wavefronts of the workgroup, in wavefront order, one tile of 16 runs at a time through LDS.
+        // The count table is overwritten: a further column pass (rows wider than CL * 64) builds it again.
         constexpr int kCH = CL < 2 ? CL : 2;                // 64-column loads per pass through LDS
         constexpr int kW = kCH * 64;                        // columns per pass
-        float* s_red = s_cnt;                               // [kWaves][16][kW] floats <= 32 KiB
+        float* s_red = reinterpret_cast<float*>(s_cnt);     // [kWaves][16][kW] floats <= 32 KiB
         for (int rt = 0; rt < RT; ++rt) {
             for (int ch = 0; ch < CL; ch += kCH) {
                 __syncthreads();
@@ -1715,14 +1714,34 @@ __device__ __forceinline__ void dense_unit(const DenseArgs& d, const DenseGroup&
                 }
             }
         }
-        (void)cvalid;
+        if (cbase + CL * 64 < D) {
+            // rebuild the count table for the next column pass (only rows wider than 128 columns get here)
+            __syncthreads();
+            for (int i = threadIdx.x; i < kDenseSlice * kDenseRows / 16; i += kDenseThreads)
+                reinterpret_cast<uint4*>(s_cnt)[i] = make_uint4(0u, 0u, 0u, 0u);
+            __syncthreads();
+            for (int f = threadIdx.x; f < tot; f += kDenseThreads) {
+                int lo = 0, hi = kDenseRows;
+#pragma unroll
+                for (int st = 0; st < 5; ++st) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_pre[mid] <= f)
+                        lo = mid;
+                    else
+                        hi = mid;
+                }
+                const int b = vals[s_p0[lo] + (f - s_pre[lo])];
+                atomicAdd(&s_cnt[(b - sl_lo) * (kDenseRows / 4) + (lo >> 2)], 1u << (8 * (lo & 3)));
+            }
+            __syncthreads();
+        }
     }
 }
 
 template <typename GT>
 __global__ __launch_bounds__(kDenseThreads, 4) void dense_rows_kernel(DenseArgs d)
 {
-    __shared__ __align__(16) float s_cnt[kDenseSub * kDenseRows];   // 32 KiB; reused for the cross-wave sums
+    __shared__ __align__(16) uint32_t s_cnt[kDenseSlice * kDenseRows / 4];   // 32 KiB; reused for the cross-wave sums
     __shared__ int32_t s_p0[kDenseRows], s_pre[kDenseRows + 1], s_slot[kDenseRows];
     const BwdArgs& a = d.b;
     const int ngroups = (int)a.counters->dense_groups;
@@ -1743,13 +1762,20 @@ __global__ __launch_bounds__(kDenseThreads, 4) void dense_rows_kernel(DenseArgs 
         const int j = local / any.ng;
         const DenseGroup grp = d.dgroup[any.gbase + (local - j * any.ng)];
         const TableMeta m = a.meta[grp.t];
-        bool nonfinite = false;
+        uint32_t dirty_bits = 0;
         // 128 columns per pass (64 for narrow tables); wider rows take further passes over the same bags
-        if (m.dim > 64)
-            dense_unit<GT, 2, 2>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, nonfinite);
-        else
-            dense_unit<GT, 2, 1>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, nonfinite);
-        if (__ballot(nonfinite) != 0ull && (threadIdx.x & (kWave - 1)) == 0)
+        if (grp.nrows > 16) {
+            if (m.dim > 64)
+                dense_unit<GT, 2, 2>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, dirty_bits);
+            else
+                dense_unit<GT, 2, 1>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, dirty_bits);
+        } else {
+            if (m.dim > 64)
+                dense_unit<GT, 1, 2>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, dirty_bits);
+            else
+                dense_unit<GT, 1, 1>(d, grp, m, j, s_cnt, s_p0, s_pre, s_slot, dirty_bits);
+        }
+        if (__ballot(dirty_bits == 0x7f800000u) != 0ull && (threadIdx.x & (kWave - 1)) == 0)
             atomicOr(&a.dense_dirty[grp.t], 1u);
     }
 }

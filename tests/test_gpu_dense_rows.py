@@ -1,5 +1,5 @@
 """GPU parity of the dense-hot-row path of the fused backward: runs longer than the call's threshold
-(max(1024, batch / 12) lookups) are summed as count matrix x gradient block, 16 runs of a table per group,
+(max(1024, batch / 8) lookups) are summed as count matrix x gradient block, 32 runs of a table per group,
 1024 bags per partial row, instead of one gathered gradient row per lookup.  The cases put many such runs
 into one table (several groups), span several bag slices with a ragged last one, use the narrowest and the
 widest rows, both layouts and all gradient types, a batch of three bags with hundreds of copies of a row per
@@ -35,7 +35,7 @@ def _spec(name, dtype):
 def _dense_runs(spec, idx, off):
     B = spec.batch
     nslices = -(-B // 1024)
-    thr = max(1024, B // 12, 128 * ((nslices + 1) // 2 + 3))
+    thr = max(1024, B // 8, 128 * ((nslices + 1) // 2 + 3))
     n = 0
     for t in range(spec.T):
         n += int((np.bincount(idx[off[t * B]:off[(t + 1) * B]], minlength=1) > thr).sum())
