@@ -98,13 +98,25 @@ def sort_passes(rows):
     return np.ceil(bits / 8.0)
 
 
-def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0, passes_t=None):
+DENSE_SLICE = 1024   # bags per partial row of a dense run (kDenseSlice)
+
+
+def dense_threshold(batch):
+    """Run length beyond which the library sums a run as counts x gradient block (dense_threshold in the library)."""
+    nslices = -(-max(batch, 1) // DENSE_SLICE)
+    return max(1024, batch // 8, 128 * ((nslices + 1) // 2 + 3))
+
+
+def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0, passes_t=None,
+                 ndense_t=None, udense_t=None):
     """Bytes one launch of each kernel must move, two ways.
     compulsory: every distinct byte once -- what an ideal cache would leave for HBM; the roofline numerator.
     logical:    every lookup counted as a row read -- a throughput figure that caches can push past the HBM peak.
-    n_t / u_t: lookups / distinct rows per table; nlong_t / ulong_t: lookups in / number of runs longer than LONG_RUN;
-    so / sg: bytes per output / gradient element; state_per_elem: float32 optimizer states per weight element
-    (0 = one moment per row); passes_t: radix passes per table (default: one pass for every table, the figure per pass).
+    n_t / u_t: lookups / distinct rows per table; nlong_t / ulong_t: lookups in / number of runs longer than LONG_RUN
+    that the update kernel splits over chunks; ndense_t / udense_t: the same for the runs beyond the dense threshold,
+    which dense_rows_kernel sums; so / sg: bytes per output / gradient element; state_per_elem: float32 optimizer
+    states per weight element (0 = one moment per row); passes_t: radix passes per table (default: one pass for
+    every table, the figure per pass).
     Sort figures are per launch: the first scatter pass reads the caller's 4-byte indices and writes key + payload
     (12 bytes per lookup), later passes read and write both (16 bytes)."""
     sw = 4 if spec.dtype == 0 else 2
@@ -112,12 +124,16 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0,
     B = float(spec.batch)
     N = float(n_t.sum())
     U = float(u_t.sum())
+    if ndense_t is None:
+        ndense_t, udense_t = np.zeros(spec.T), np.zeros(spec.T)
     bags = float(spec.T) * B
     io_fwd = N * 4 + bags * 8 + (B * so * D).sum()
     state_rw = 8 * D * state_per_elem if state_per_elem else 8.0
-    rmw = (u_t * (2 * D * sw + state_rw)).sum()
+    row_rw = 2 * D * sw + state_rw                       # a table row and its optimizer state, read + written
     slab = B * sg * D
-    partial_rows = nlong_t / 128.0 + 2 * ulong_t    # one fp32 partial row per chunk a long run touches
+    partial_rows = nlong_t / 128.0 + 2 * ulong_t         # one fp32 partial row per chunk a long run touches
+    dense_rows = udense_t * float(-(-spec.batch // DENSE_SLICE))   # one fp32 partial row per 1024-bag slice
+    n_upd = n_t - ndense_t                               # lookups the update kernel gathers
     if passes_t is None:
         scatter = N * 16
         hist = N * 4
@@ -132,13 +148,16 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0,
         "radix_scatter": scatter,
         "radix_scan": 0.0,
         "runlength": N * 4 + U * 8,
-        "reduce_update": float(N * 4 + U * 8 + np.minimum(n_t * sg * D, slab).sum() + rmw +
-                               (partial_rows * 4 * D).sum()),
-        "long_fixup": float((partial_rows * 4 * D + ulong_t * (2 * D * sw + state_rw)).sum()),
+        # payloads + run descriptors + each gradient row once + the rows it updates itself + its partial rows
+        "reduce_update": float(n_upd.sum() * 4 + U * 8 + np.minimum(n_upd * sg * D, slab).sum() +
+                               ((u_t - ulong_t - udense_t) * row_rw).sum() + (partial_rows * 4 * D).sum()),
+        # payloads of the dense runs + the gradient block of every table that has dense runs + its partial rows
+        "dense_rows": float(ndense_t.sum() * 4 + (np.where(udense_t > 0, slab, 0.0)).sum() + (dense_rows * 4 * D).sum()),
+        "long_fixup": float(((partial_rows + dense_rows) * 4 * D + (ulong_t + udense_t) * row_rw).sum()),
     }
     logical = dict(comp)
     logical["forward"] = float((n_t * D * sw).sum() + io_fwd)
-    logical["reduce_update"] = float(N * 4 + U * 8 + (n_t * sg * D).sum() + rmw + (partial_rows * 4 * D).sum())
+    logical["reduce_update"] = float(comp["reduce_update"] - np.minimum(n_upd * sg * D, slab).sum() + (n_upd * sg * D).sum())
     return comp, logical
 
 
@@ -559,6 +578,8 @@ def run_workload(args, spec, dev, headline):
     n_t = per_table_counts(spec, last).astype(np.float64)
     nlong_t = np.zeros(spec.T)
     ulong_t = np.zeros(spec.T)
+    ndense_t = np.zeros(spec.T)
+    udense_t = np.zeros(spec.T)
     longest_run = 0
     if args.fwd_only:
         u_t = np.zeros(spec.T)
@@ -572,12 +593,17 @@ def run_workload(args, spec, dev, headline):
         u_t = torch.bincount(tab, minlength=spec.T).cpu().numpy().astype(np.float64)
         lens = torch.diff(art["seg_offsets"].to(torch.int64))
         longest_run = int(lens.max().item()) if lens.numel() else 0
-        is_long = lens > LONG_RUN
+        thr = dense_threshold(spec.batch)
+        is_dense = lens > (thr if last.num_indices > thr else (1 << 62))
+        is_long = (lens > LONG_RUN) & ~is_dense
         nlong_t = torch.bincount(tab[is_long], weights=lens[is_long].double(), minlength=spec.T).cpu().numpy()
         ulong_t = torch.bincount(tab[is_long], minlength=spec.T).cpu().numpy().astype(np.float64)
-        del art, uk, tab, lens, is_long
+        ndense_t = torch.bincount(tab[is_dense], weights=lens[is_dense].double(), minlength=spec.T).cpu().numpy()
+        udense_t = torch.bincount(tab[is_dense], minlength=spec.T).cpu().numpy().astype(np.float64)
+        del art, uk, tab, lens, is_long, is_dense
     comp, logical = kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=out.element_size(), sg=grad.element_size(),
-                                 state_per_elem={0: 0, 1: 1, 2: 2}[opt_id], passes_t=sort_passes(spec.rows))
+                                 state_per_elem={0: 0, 1: 1, 2: 2}[opt_id], passes_t=sort_passes(spec.rows),
+                                 ndense_t=ndense_t, udense_t=udense_t)
 
     kernels = {}
     for name, (launches, ms) in prof.items():
@@ -642,6 +668,8 @@ def run_workload(args, spec, dev, headline):
             "lookups_per_step": lookups / args.steps,
             "unique_rows_last_step": num_unique,
             "longest_duplicate_run_last_step": longest_run,
+            "dense_runs_last_step": int(udense_t.sum()),
+            "lookups_in_dense_runs_last_step": int(ndense_t.sum()),
             "table_bytes": spec.weight_bytes,
             "workspace_bytes": int(op.sizes["workspace_bytes"]),
             "index_dist": spec.index_dist if spec.index_dist == "uniform" else f"zipf({spec.zipf_s})",

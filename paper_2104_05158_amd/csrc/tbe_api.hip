@@ -75,7 +75,8 @@ struct tbe_s {
     int dmax = 0;
     int fwd_epl = 4;
     int fwd_kmax = 1;
-    int key_bits = 1;
+    int key_bits = 1;                   // bits of the tallest table's row index
+    std::vector<int> pass_digit_bits;   // per sort launch: the widest digit any table sorts in it
     std::vector<int64_t> woff;      // T+1, elements
     std::vector<int64_t> soff;      // T+1, rows
     std::vector<int32_t> coloff;    // T+1
@@ -378,6 +379,22 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
     h->key_bits = 1;
     while (h->key_bits < 32 && ((int64_t)1 << h->key_bits) < max_rows)
         ++h->key_bits;
+    // per-table sort geometry: table t orders ceil(log2 H_t) bits in P_t = ceil(bits / 8) passes during the
+    // last P_t of the P launches, bits split as evenly as possible (wider digits first)
+    const int P = (int)ceil_div(h->key_bits, 8);
+    h->pass_digit_bits.assign(P, 1);
+    std::vector<int> table_bits(cfg->num_tables, 1);
+    for (int t = 0; t < cfg->num_tables; ++t) {
+        int b = 1;
+        while (b < 32 && ((int64_t)1 << b) < cfg->rows[t])
+            ++b;
+        table_bits[t] = b;
+        const int pt = (b + 7) / 8, q = b / pt, rem = b - q * pt;
+        for (int lp = 0; lp < pt; ++lp) {
+            int& w = h->pass_digit_bits[P - pt + lp];
+            w = std::max(w, q + (lp < rem ? 1 : 0));
+        }
+    }
 
     h->woff.resize(h->T + 1);
     h->soff.resize(h->T + 1);
@@ -396,7 +413,7 @@ tbe_status_t tbe_create(const tbe_config_t* cfg, tbe_handle_t* out_handle)
         m.col = c;
         m.lpr_fwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], h->fwd_epl)));
         m.lpr_bwd = std::min(6, pow2ceil_log2((int)ceil_div(h->dims[t], 8)));
-        m.pad = 0;
+        m.key_bits = table_bits[t];
         w += h->rows[t] * (int64_t)h->dims[t];
         s += h->rows[t];
         c += h->dims[t];
@@ -538,48 +555,43 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
         TBE_LAUNCH_CHECK(h, "sort_plan kernels");
     }
 
-    // a3: stable LSD radix sort, segmented by table, over only the significant bits of the row index
+    // a3: stable LSD radix sort, segmented by table; every table over the bits of its own row index, in its own
+    // number of passes, all tables finishing in the last launch (tables with fewer passes sit out the first ones)
     const int passes = (int)ceil_div(h->key_bits, 8);
     uint32_t* hist = h->ws<uint32_t>(h->off_hist);
-    const uint32_t* in_keys = reinterpret_cast<const uint32_t*>(d_indices);
-    const int32_t* in_vals = nullptr;
-    int cur = -1, shift = 0;  // cur: pair that holds the current order (-1 = the caller's arrays)
+    const TableMeta* meta = h->ws<TableMeta>(h->off_meta);
+    const uint32_t* indices = reinterpret_cast<const uint32_t*>(d_indices);
+    int cur = -1;  // pair that holds the current order (-1 = nothing sorted yet)
     for (int p = 0; p < passes; ++p) {
-        const int bits = h->key_bits / passes + (p < h->key_bits % passes ? 1 : 0);
+        const int nd_bits = h->pass_digit_bits[p];   // widest digit any table sorts in this launch
         const int out = cur < 0 ? 0 : cur ^ 1;
+        const uint32_t* keys_cur = cur < 0 ? indices : keys[cur];
+        const int32_t* vals_cur = cur < 0 ? nullptr : vals[cur];
         {
             ScopedTimer tm(h, SLOT_RADIX_HIST, st);
-            hipLaunchKernelGGL(radix_hist_kernel, dim3(max_tiles), dim3(kSortThreads), 0, st, pl, in_keys, hist,
-                               shift, bits);
+            hipLaunchKernelGGL(radix_hist_kernel, dim3(max_tiles), dim3(kSortThreads), 0, st, pl, meta, keys_cur,
+                               indices, hist, p, passes, nd_bits);
             TBE_LAUNCH_CHECK(h, "radix_hist_kernel");
         }
         {
             ScopedTimer tm(h, SLOT_RADIX_SCAN, st);
-            rc = device_scan(h, hist, (int64_t)max_tiles << bits, nullptr, st);
+            rc = device_scan(h, hist, (int64_t)max_tiles << nd_bits, nullptr, st);
             if (rc != TBE_OK)
                 return rc;
         }
         {
             ScopedTimer tm(h, SLOT_RADIX_SCATTER, st);
-            const bool first = p == 0, last = p == passes - 1;
-#define SCATTER(F, L)                                                                                          \
-    hipLaunchKernelGGL((radix_scatter_kernel<F, L>), dim3(max_tiles), dim3(kSortThreads), 0, st, pl, in_keys, \
-                       in_vals, keys[out], vals[out], hist, d_offsets, row_base, batch, shift, bits)
-            if (first && last)
-                SCATTER(true, true);
-            else if (first)
-                SCATTER(true, false);
-            else if (last)
-                SCATTER(false, true);
+            if (p == passes - 1)
+                hipLaunchKernelGGL((radix_scatter_kernel<true>), dim3(max_tiles), dim3(kSortThreads), 0, st, pl, meta,
+                                   keys_cur, vals_cur, indices, keys[out], vals[out], hist, d_offsets, row_base, batch,
+                                   p, passes, nd_bits);
             else
-                SCATTER(false, false);
-#undef SCATTER
+                hipLaunchKernelGGL((radix_scatter_kernel<false>), dim3(max_tiles), dim3(kSortThreads), 0, st, pl, meta,
+                                   keys_cur, vals_cur, indices, keys[out], vals[out], hist, d_offsets, row_base, batch,
+                                   p, passes, nd_bits);
             TBE_LAUNCH_CHECK(h, "radix_scatter_kernel");
         }
         cur = out;
-        in_keys = keys[cur];
-        in_vals = vals[cur];
-        shift += bits;
     }
     h->final_buf = cur;
 

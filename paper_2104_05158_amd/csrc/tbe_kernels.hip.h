@@ -52,7 +52,7 @@ struct TableMeta {      // 32 bytes, one per table, in the workspace head
     int32_t col;        // first output column
     int32_t lpr_fwd;    // log2 lanes per row, forward (EPL elements per lane)
     int32_t lpr_bwd;    // log2 lanes per row, backward (2 x 4 floats per lane)
-    int32_t pad;
+    int32_t key_bits;   // ceil(log2 rows) (at least 1): the bits of the table's row index that the sort orders
 };
 
 struct Counters {       // workspace scalars
@@ -330,6 +330,12 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
 // over the whole array then yields global output positions, because every table's counts add up to
 // exactly its number of lookups.
 //
+// Every table is sorted over its own ceil(log2 H_t) index bits in ceil(bits / 8) passes of equal-as-possible
+// digit widths.  A launch serves all tables; a table that needs fewer passes than the tallest one sits out
+// the first launches (its tiles report all their keys under digit 0, so the scan still yields global
+// positions, and move nothing) and makes its first pass -- the one that reads the caller's indices -- later,
+// so that every table finishes in the same launch and in the same buffer.
+//
 // Per pass: (1) per-tile digit histogram, (2) the scan, (3) scatter: every wavefront ranks its
 // 16 x 64 keys with ballot-based digit matching into per-wave LDS counters, the tile is reordered by
 // digit inside LDS and then written out in runs that are contiguous in global memory.  Order inside
@@ -454,6 +460,28 @@ __device__ __forceinline__ bool tile_geom(const SortPlan& pl, int g, int nd, Til
     return true;
 }
 
+// Where table t stands in launch p of P: P_t = ceil(bits / 8) passes, the last P_t launches; pass lp orders
+// `width` bits starting at `shift` (the bits are split as evenly as possible, wider digits first).
+struct PassGeom {
+    bool active;     // the table takes part in this launch
+    bool first;      // this is the table's first pass: keys come from the caller's indices
+    int shift, width;
+};
+
+__device__ __forceinline__ PassGeom pass_geom(int key_bits, int p, int P)
+{
+    const int pt = (key_bits + 7) >> 3;
+    const int lp = p - (P - pt);
+    PassGeom g;
+    g.active = lp >= 0;
+    g.first = lp == 0;
+    const int q = key_bits / pt, rem = key_bits - q * pt;
+    const int l = max(lp, 0);
+    g.width = q + (l < rem ? 1 : 0);
+    g.shift = l * q + min(l, rem);
+    return g;
+}
+
 // Lanes of the wavefront whose digit equals this lane's (valid lanes only).  Bit b of every lane is
 // broadcast by a ballot; a lane keeps the lanes whose bit agrees with its own.  The loop is unrolled
 // for the largest digit width with a uniform guard, so no bit position costs a loop iteration.
@@ -479,19 +507,30 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t dg, bool valid, int bit
 }
 
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
-    SortPlan pl, const uint32_t* __restrict__ keys, uint32_t* __restrict__ hist, int shift, int bits)
+    SortPlan pl, const TableMeta* __restrict__ meta, const uint32_t* __restrict__ keys_cur,
+    const uint32_t* __restrict__ indices, uint32_t* __restrict__ hist, int p, int P, int nd_bits)
 {
     __shared__ uint32_t s_hist[256];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int nd = 1 << bits;
-    const uint32_t mask = nd - 1;
+    const int nd = 1 << nd_bits;
     TileGeom tg;
     if (!tile_geom(pl, blockIdx.x, nd, tg))
         return;
+    const PassGeom pg = pass_geom(meta[tg.t].key_bits, p, P);
+    if (!pg.active) {
+        // the table sits this launch out: all its keys count under digit 0
+        if ((int)threadIdx.x < nd)
+            hist[tg.hbase + (int64_t)threadIdx.x * tg.hstride] = threadIdx.x == 0 ? (uint32_t)tg.cnt : 0u;
+        return;
+    }
+    const uint32_t* __restrict__ keys = pg.first ? indices : keys_cur;
+    const int shift = pg.shift;
+    const uint32_t mask = (1u << pg.width) - 1u;
     const int base = tg.first + wave * (kSortTile / (kSortThreads / kWave));
     const int end = tg.first + tg.cnt;
-    // all 16 key loads are issued before the first one is used (positions past the tile are clamped)
+    // all 16 key loads are issued before the first one is used (positions past the tile are clamped);
+    // 16-byte loads of four keys per lane were measured and are not faster
     uint32_t key[kSortKeysPerThread];
 #pragma unroll
     for (int r = 0; r < kSortKeysPerThread; ++r)
@@ -522,14 +561,16 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
         hist[tg.hbase + (int64_t)threadIdx.x * tg.hstride] = s_hist[threadIdx.x];
 }
 
-// FIRST: keys_in is the caller's index array and the payload is computed from the offsets;
-// LAST: the table's row base is added to the keys that are written out.
-template <bool FIRST, bool LAST>
+// A table's first pass reads the caller's index array as keys and computes the payload from the offsets;
+// LAST (the launch in which every table makes its last pass): the table's row base is added to the keys
+// that are written out.
+template <bool LAST>
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
-    SortPlan pl, const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
+    SortPlan pl, const TableMeta* __restrict__ meta, const uint32_t* __restrict__ keys_cur,
+    const int32_t* __restrict__ vals_in, const uint32_t* __restrict__ indices,
     uint32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
     const uint32_t* __restrict__ hist_scanned, const int64_t* __restrict__ offsets,
-    const uint32_t* __restrict__ row_base, int32_t B, int shift, int bits)
+    const uint32_t* __restrict__ row_base, int32_t B, int p, int P, int nd_bits)
 {
     constexpr int kWaves = kSortThreads / kWave;
     __shared__ uint32_t s_keys[kSortTile];
@@ -540,11 +581,17 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int nd = 1 << bits;
-    const uint32_t mask = nd - 1;
+    const int nd = 1 << nd_bits;
     TileGeom tg;
     if (!tile_geom(pl, blockIdx.x, nd, tg))
         return;
+    const PassGeom pg = pass_geom(meta[tg.t].key_bits, p, P);
+    if (!pg.active)
+        return;                                  // the table sits this launch out: nothing moves
+    const bool FIRST = pg.first;
+    const int shift = pg.shift, bits = pg.width;
+    const uint32_t mask = (1u << bits) - 1u;
+    const uint32_t* __restrict__ keys_in = FIRST ? indices : keys_cur;
     const int tile_cnt = tg.cnt;
     const int end = tg.first + tile_cnt;
 
@@ -1293,7 +1340,7 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     int t = -1;
     uint32_t t_lo = 1u, t_hi = 0u;  // empty range: the first key always seeks
     TableMeta m;
-    m.woff = 0; m.rbase = 0; m.dim = 4; m.col = 0; m.lpr_fwd = 0; m.lpr_bwd = 0; m.pad = 0;
+    m.woff = 0; m.rbase = 0; m.dim = 4; m.col = 0; m.lpr_fwd = 0; m.lpr_bwd = 0; m.key_bits = 1;
     auto seek_table = [&](uint32_t key) {
         if (key < t_lo || key >= t_hi) {
             t = find_table(a.row_base, a.T, key);

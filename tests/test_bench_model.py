@@ -20,7 +20,7 @@ def test_kernel_bytes_on_a_hand_counted_case():
     assert logical["reduce_update"] == N * 4 + U * 8 + (10 * 4 * 8 + 6 * 4 * 16) + rmw == 1392
     assert comp["radix_hist"] == N * 4 and comp["radix_scatter"] == N * 16
     assert comp["runlength"] == N * 4 + U * 8
-    assert comp["long_fixup"] == 0
+    assert comp["long_fixup"] == 0 and comp["dense_rows"] == 0
 
 
 def test_long_runs_add_partial_rows_and_16_bit_types_halve_the_row_bytes():
@@ -30,8 +30,17 @@ def test_long_runs_add_partial_rows_and_16_bit_types_halve_the_row_bytes():
     # one run of 1280 lookups: a partial fp32 row per 128 positions plus two ragged ends, written and read once
     with_long, _ = bench.kernel_bytes(spec, n_t, u_t, np.array([1280.0]), np.array([1.0]))
     rows = 1280 / 128 + 2
-    assert with_long["reduce_update"] - base["reduce_update"] == rows * 4 * 64
+    # the update kernel writes the partial rows and no longer updates that row itself; the fix-up reads them and does
+    assert with_long["reduce_update"] - base["reduce_update"] == rows * 4 * 64 - (2 * 64 * 4 + 8)
     assert with_long["long_fixup"] == rows * 4 * 64 + (2 * 64 * 4 + 8)
+    # the same run beyond the dense threshold: its lookups leave the update kernel; dense_rows reads their payloads
+    # and the table's gradient block once and writes one partial row per 1024-bag slice (2 here)
+    with_dense, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(1), np.zeros(1), ndense_t=np.array([1280.0]),
+                                       udense_t=np.array([1.0]))
+    assert with_dense["dense_rows"] == 1280 * 4 + 2048 * 4 * 64 + 2 * 4 * 64
+    assert with_dense["long_fixup"] == 2 * 4 * 64 + (2 * 64 * 4 + 8)
+    assert base["reduce_update"] - with_dense["reduce_update"] == 1280 * 4 + (2 * 64 * 4 + 8)
+    assert bench.dense_threshold(65536) == 8192 and bench.dense_threshold(700) == 1024 and bench.dense_threshold(16384) == 2048
     half, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(1), np.zeros(1), so=2, sg=2)
     assert base["forward"] - half["forward"] == 2048 * 2 * 64
     assert base["reduce_update"] - half["reduce_update"] == min(5000, 2048) * 2 * 64

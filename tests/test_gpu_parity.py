@@ -97,6 +97,18 @@ def test_widest_key_needs_four_passes(gpu_device):
     tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="bits25")
 
 
+def test_tables_with_different_pass_counts_in_one_sort(gpu_device):
+    # row-index bits 2, 8, 9, 16, 17 and 25 side by side: 1, 1, 2, 2, 3 and 4 radix passes of different digit
+    # widths; the short tables sit out the first launches and read the caller's indices later, and every
+    # table must still end in the same buffer, several 8192-position tiles each
+    rows = [3, 256, 300, 65536, 70_000, (1 << 24) + 5]
+    spec = wl.custom(rows, [4, 8, 4, 4, 8, 4], 0, 1200, [30.0, 25.0, 20.0, 22.0, 28.0, 24.0], name="mixed_passes")
+    idx, off, w, g = _np_case(spec, 21)
+    idx[int(off[5 * 1200]):int(off[5 * 1200]) + 3] = [1 << 24, (1 << 24) + 4, 0]     # the tallest table's extreme rows occur
+    assert int(off[1200]) > 2 * 8192
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="mixed_passes")
+
+
 def test_segmented_sort_tables_without_lookups(gpu_device):
     # tables 0, 2 and 4 receive no lookup at all: they own no sort tile and their rows stay untouched
     spec = wl.custom([50, 3000, 7, 120, 9000], [8, 16, 4, 32, 8], 0, 300, [0.0, 40.0, 0.0, 12.0, 0.0],
