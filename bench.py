@@ -3,7 +3,7 @@
 
 A step = one pass of the whole path over one synthetic batch: tbe_forward, then
 tbe_backward_rowwise_adagrad (sort plan, radix sort, run-length, fused reduce + row-wise AdaGrad,
-dense hot rows, fix-up) on the same batch.  Inputs, weights and optimizer state are resident in HBM
+long runs by bag window, dense hot rows, fix-up) on the same batch.  Inputs, weights and optimizer state are resident in HBM
 before the timed region; a rotation of pre-generated batches (different seeds) is used so that no step
 re-reads the previous step's index stream.
 
@@ -88,7 +88,20 @@ def per_table_counts(spec, batch):
     return np.diff(bounds.cpu().numpy())
 
 
-LONG_RUN = 512    # runs longer than this are cut at 128-position chunk borders by the library (kLongRun)
+LONG_RUN = 512    # runs longer than this are summed in pieces (kLongRun): by bag window, or as dense rows
+
+
+def window_count(batch, D, grad_bytes):
+    """Bag windows the library cuts a long run of a D-column table into (window_geom in the library): about 2 MiB
+    of the table's gradient block per window, at most 16 windows."""
+    bags = 1024
+    while bags * 2 * D * grad_bytes <= (2 << 20):
+        bags *= 2
+    nwin = -(-batch // bags)
+    if nwin > 16:
+        bags = -(-(-(-batch // 16)) // 1024) * 1024
+        nwin = -(-batch // bags)
+    return max(nwin, 1)
 
 
 def sort_passes(rows):
@@ -108,13 +121,13 @@ def dense_threshold(batch):
 
 
 def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0, passes_t=None,
-                 ndense_t=None, udense_t=None):
+                 ndense_t=None, udense_t=None, long_rows_t=None):
     """Bytes one launch of each kernel must move, two ways.
     compulsory: every distinct byte once -- what an ideal cache would leave for HBM; the roofline numerator.
     logical:    every lookup counted as a row read -- a throughput figure that caches can push past the HBM peak.
     n_t / u_t: lookups / distinct rows per table; nlong_t / ulong_t: lookups in / number of runs longer than LONG_RUN
-    that the update kernel splits over chunks; ndense_t / udense_t: the same for the runs beyond the dense threshold,
-    which dense_rows_kernel sums; so / sg: bytes per output / gradient element; state_per_elem: float32 optimizer
+    that window_runs_kernel sums piece by piece (long_rows_t: their partial rows, default one per 128 lookups + 2);
+    ndense_t / udense_t: the same for the runs beyond the dense threshold, which dense_rows_kernel sums; so / sg: bytes per output / gradient element; state_per_elem: float32 optimizer
     states per weight element (0 = one moment per row); passes_t: radix passes per table (default: one pass for
     every table, the figure per pass).
     Sort figures are per launch: the first scatter pass reads the caller's 4-byte indices and writes key + payload
@@ -131,9 +144,9 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0,
     state_rw = 8 * D * state_per_elem if state_per_elem else 8.0
     row_rw = 2 * D * sw + state_rw                       # a table row and its optimizer state, read + written
     slab = B * sg * D
-    partial_rows = nlong_t / 128.0 + 2 * ulong_t         # one fp32 partial row per chunk a long run touches
+    partial_rows = nlong_t / 128.0 + 2 * ulong_t if long_rows_t is None else long_rows_t   # fp32 partial rows of long runs
     dense_rows = udense_t * float(-(-spec.batch // DENSE_SLICE))   # one fp32 partial row per 1024-bag slice
-    n_upd = n_t - ndense_t                               # lookups the update kernel gathers
+    n_upd = n_t - ndense_t - nlong_t                     # lookups the update kernel gathers itself
     if passes_t is None:
         scatter = N * 16
         hist = N * 4
@@ -148,9 +161,12 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0,
         "radix_scatter": scatter,
         "radix_scan": 0.0,
         "runlength": N * 4 + U * 8,
-        # payloads + run descriptors + each gradient row once + the rows it updates itself + its partial rows
+        # payloads + run descriptors + each gradient row once + the rows it updates itself
         "reduce_update": float(n_upd.sum() * 4 + U * 8 + np.minimum(n_upd * sg * D, slab).sum() +
-                               ((u_t - ulong_t - udense_t) * row_rw).sum() + (partial_rows * 4 * D).sum()),
+                               ((u_t - ulong_t - udense_t) * row_rw).sum()),
+        # payloads of the long runs + each gradient row they touch once + their partial rows + 16-byte piece records
+        "window_runs": float(nlong_t.sum() * 4 + np.minimum(nlong_t * sg * D, slab).sum() +
+                             (partial_rows * (4 * D + 32)).sum()),
         # payloads of the dense runs + the gradient block of every table that has dense runs + its partial rows
         "dense_rows": float(ndense_t.sum() * 4 + (np.where(udense_t > 0, slab, 0.0)).sum() + (dense_rows * 4 * D).sum()),
         "long_fixup": float(((partial_rows + dense_rows) * 4 * D + (ulong_t + udense_t) * row_rw).sum()),
@@ -580,6 +596,7 @@ def run_workload(args, spec, dev, headline):
     ulong_t = np.zeros(spec.T)
     ndense_t = np.zeros(spec.T)
     udense_t = np.zeros(spec.T)
+    long_rows_t = None
     longest_run = 0
     if args.fwd_only:
         u_t = np.zeros(spec.T)
@@ -598,12 +615,24 @@ def run_workload(args, spec, dev, headline):
         is_long = (lens > LONG_RUN) & ~is_dense
         nlong_t = torch.bincount(tab[is_long], weights=lens[is_long].double(), minlength=spec.T).cpu().numpy()
         ulong_t = torch.bincount(tab[is_long], minlength=spec.T).cpu().numpy().astype(np.float64)
+        # partial rows of a long run: one per window piece; a run with fewer slots than windows (two per fully
+        # covered 128-position chunk) merges windows in twos or fours
+        nwin_t = torch.tensor([window_count(spec.batch, int(d), grad.element_size()) for d in spec.dims], device=dev)
+        seg = art["seg_offsets"].to(torch.int64)
+        slots = 2 * ((seg[1:] - 1) // 128 - seg[:-1] // 128 - 1)
+        nw = nwin_t[tab]
+        step = torch.ones_like(nw)
+        for _ in range(4):
+            step = torch.where(-(-nw // step) > slots, step * 2, step)
+        pieces = -(-nw // step)
+        long_rows_t = torch.bincount(tab[is_long], weights=pieces[is_long].double(), minlength=spec.T).cpu().numpy()
+        del seg, slots, nw, pieces, step
         ndense_t = torch.bincount(tab[is_dense], weights=lens[is_dense].double(), minlength=spec.T).cpu().numpy()
         udense_t = torch.bincount(tab[is_dense], minlength=spec.T).cpu().numpy().astype(np.float64)
         del art, uk, tab, lens, is_long, is_dense
     comp, logical = kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=out.element_size(), sg=grad.element_size(),
                                  state_per_elem={0: 0, 1: 1, 2: 2}[opt_id], passes_t=sort_passes(spec.rows),
-                                 ndense_t=ndense_t, udense_t=udense_t)
+                                 ndense_t=ndense_t, udense_t=udense_t, long_rows_t=long_rows_t)
 
     kernels = {}
     for name, (launches, ms) in prof.items():

@@ -32,16 +32,18 @@ enum Slot {
     SLOT_RADIX_SCATTER,
     SLOT_RUNLENGTH,
     SLOT_REDUCE_UPDATE,
+    SLOT_WINDOW_RUNS,
     SLOT_DENSE_ROWS,
     SLOT_LONG_FIXUP,
     SLOT_COUNT
 };
 const char* const kSlotNames[SLOT_COUNT] = {"forward",       "sort_plan",  "radix_hist",    "radix_scan",
-                                            "radix_scatter", "runlength",  "reduce_update", "dense_rows", "long_fixup"};
+                                            "radix_scatter", "runlength",  "reduce_update", "window_runs", "dense_rows", "long_fixup"};
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 constexpr int kDenseGrid = 1024;
+constexpr int kWindowGrid = 1024;  // persistent workgroups of window_runs_kernel: 8 wavefronts per CU, a multiple of 8
 constexpr int kDenseBagsPerLookup = 8;   // persistent workgroups of dense_rows_kernel: 4 per CU, a multiple of 8
 
 inline int pow2ceil_log2(int x)
@@ -88,6 +90,7 @@ struct tbe_s {
     int64_t max_tiles = 1;
     size_t off_hist = 0, off_scan_tmp = 0, off_rl_counts = 0, off_chunk_first = 0, off_partials = 0;
     size_t off_long_list = 0, off_zero = 0, workspace_bytes = 0;
+    size_t off_win_cnt = 0, off_win_list = 0, off_wrun = 0, off_wbounds = 0;
     size_t off_dense_dirty = 0, off_dense_cnt = 0, off_dense_list = 0, off_drun = 0, off_dgroup = 0, off_dbounds = 0;
     int64_t dbounds_cap = 0;   // entries
     size_t weight_bytes = 0, state_bytes = 0;
@@ -232,6 +235,12 @@ void plan_workspace(tbe_s* h)
             break;
     }
     h->off_dbounds = take(4 * (size_t)h->dbounds_cap);
+    // long runs below the dense threshold: per-table queues, the prefix of their lengths, and the runs' piece records
+    const int64_t win_runs_max = nmax / kLongRun + h->T + 2;
+    h->off_win_cnt = take(4 * (size_t)h->T);
+    h->off_win_list = take(4 * (size_t)win_runs_max);
+    h->off_wrun = take(4 * 2 * (size_t)(h->T + 1));   // prefixes of the per-table queue lengths and piece counts
+    h->off_wbounds = take(sizeof(WinPiece) * (size_t)win_runs_max * kWinMax);   // the runs' piece records
     h->workspace_bytes = off;
 }
 
@@ -489,6 +498,7 @@ tbe_status_t tbe_bind(tbe_handle_t h, void* d_weights, float* d_state, void* d_w
     TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_zero, 0, kZeroRowBytes));
     TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_dense_cnt, 0, 4 * (size_t)h->T));
     TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_dense_dirty, 0, 4 * (size_t)h->T));
+    TBE_HIP_CHECK(h, hipMemset(h->d_ws + h->off_win_cnt, 0, 4 * (size_t)h->T));
     TBE_HIP_CHECK(h, hipDeviceSynchronize());
     h->bound = true;
     h->final_buf = -1;
@@ -627,18 +637,32 @@ static void launch_update(const BwdArgs& a, dim3 grid, dim3 grid_fix, hipStream_
         ScopedTimer tm(h, SLOT_REDUCE_UPDATE, st);
         hipLaunchKernelGGL((reduce_update_kernel<WT, GT, OPT>), grid, dim3(kBwdThreads), 0, st, a);
     }
+    Counters* counters = h->ws<Counters>(h->off_counters);
+    if (a.n > kLongRun) {
+        // the long runs below the dense threshold: plan -> window-border positions -> pieces, window by window
+        ScopedTimer tm(h, SLOT_WINDOW_RUNS, st);
+        uint32_t* wpre = h->ws<uint32_t>(h->off_wrun);
+        uint32_t* ppre = wpre + (h->T + 1);
+        WinPiece* pieces = h->ws<WinPiece>(h->off_wbounds);
+        hipLaunchKernelGGL(window_plan_kernel, dim3(1), dim3(256), 0, st, a, wpre, ppre);
+        hipLaunchKernelGGL(window_pieces_kernel, dim3(1024), dim3(256), 0, st, a, wpre, ppre, pieces);
+        hipLaunchKernelGGL((window_runs_kernel<GT>), dim3(kWindowGrid), dim3(kBwdThreads), 0, st, a, pieces);
+    }
     if (a.dense_thr != INT32_MAX) {
-        // the runs the update kernel queued as dense: plan -> bag-range positions -> counts x gradient block
+        // the runs the update kernel queued as dense: plan -> bag-slice positions -> counts x gradient block
         ScopedTimer tm(h, SLOT_DENSE_ROWS, st);
         DenseArgs d;
         d.b = a;
         d.drun = h->ws<uint32_t>(h->off_drun);
         d.dgroup = h->ws<DenseGroup>(h->off_dgroup);
         d.dbounds = h->ws<int32_t>(h->off_dbounds);
-        d.nsub = (int32_t)ceil_div(a.batch, kDenseSlice);
-        hipLaunchKernelGGL(dense_plan_kernel, dim3(1), dim3(256), 0, st, a, h->ws<uint32_t>(h->off_drun),
-                           h->ws<DenseGroup>(h->off_dgroup));
-        hipLaunchKernelGGL(dense_bounds_kernel, dim3(512), dim3(256), 0, st, d);
+        d.nruns = &counters->dense_runs;
+        d.nsub = a.dense_slices;
+        d.slice_bags = kDenseSlice;
+        hipLaunchKernelGGL(run_plan_kernel, dim3(1), dim3(256), 0, st, a, a.dense_cnt, a.dense_list, a.dense_thr,
+                           (int)kDenseRows, h->ws<uint32_t>(h->off_drun), h->ws<DenseGroup>(h->off_dgroup),
+                           &counters->dense_runs, &counters->dense_groups, a.dense_dirty);
+        hipLaunchKernelGGL(run_bounds_kernel, dim3(512), dim3(256), 0, st, d);
         hipLaunchKernelGGL((dense_rows_kernel<GT>), dim3(kDenseGrid), dim3(kDenseThreads), 0, st, d);
     }
     {
@@ -724,6 +748,9 @@ static tbe_status_t enqueue_update(tbe_s* h, const void* d_grad_out, const OptCa
     a.dense_cnt = h->ws<uint32_t>(h->off_dense_cnt);
     a.dense_list = h->ws<uint32_t>(h->off_dense_list);
     a.dense_dirty = h->ws<uint32_t>(h->off_dense_dirty);
+    a.win_cnt = h->ws<uint32_t>(h->off_win_cnt);
+    a.win_list = h->ws<uint32_t>(h->off_win_list);
+    a.grad_bytes = h->grad_dtype == TBE_DTYPE_FP32 ? 4 : 2;
     a.opt.state0 = h->d_state;
     a.opt.state1 = h->optimizer == TBE_OPT_ADAM ? h->d_state + h->weight_elems : h->d_state;
     a.opt.lr = oc.lr;

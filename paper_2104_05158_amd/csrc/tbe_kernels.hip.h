@@ -33,7 +33,9 @@ constexpr int kRlThreads = 256;
 constexpr int kRlPerThread = 16;
 constexpr int kRlTile = kRlThreads * kRlPerThread;            // 4096 sorted positions
 constexpr int kChunk = 128;               // sorted positions owned by one wavefront in the update
-constexpr int kLongRun = 512;             // runs longer than this are split over their chunks
+constexpr int kLongRun = 512;             // runs longer than this are summed in pieces by other kernels (window / dense path)
+constexpr int kWinMax = 16;               // most bag windows a long run is cut into
+constexpr int kWinBatch = 8;               // pieces a workgroup of window_runs_kernel claims at a time
 constexpr int kBwdThreads = 256;          // 4 wavefronts = 4 chunks per workgroup
 constexpr int kBwdUnroll = 4;             // gradient rows in flight per lane group (long runs)
 constexpr int kShortRun = 4;              // runs up to this length are handled one per lane group
@@ -42,7 +44,7 @@ constexpr int kMaxDim = 512;
 constexpr int kDenseRows = 32;            // most runs per group: they share one pass over the table's gradient block
 constexpr int kDenseSlice = 1024;         // bags per work unit = per count table in LDS = per partial row of a dense run
 constexpr int kDenseThreads = 256;
-constexpr int kDenseMinRun = 1024;        // no run of this length or less is ever treated as dense
+constexpr int kDenseMinRun = 1024;        // no run of this length or less is ever treated as dense (> kLongRun)
 constexpr int kZeroRowBytes = 4096;        // a row of zeros in the workspace (largest row: 512 x fp32 = 2 KiB)
 
 struct TableMeta {      // 32 bytes, one per table, in the workspace head
@@ -64,9 +66,14 @@ struct Counters {       // workspace scalars
     uint32_t long_count;
     uint32_t fixup_done;        // workgroups of the running fix-up kernel that have finished
     uint32_t check_flags;       // written only by tbe_check_inputs
-    uint32_t dense_runs;        // written by dense_plan_kernel: dense runs / groups of this update
+    uint32_t dense_runs;        // written by the plan kernels: dense runs / groups, windowed runs of this update
     uint32_t dense_groups;
-    uint32_t pad[1];
+    uint32_t win_runs;          // windowed runs / their pieces of this update (written by window_plan_kernel)
+    uint32_t win_pieces;
+    uint32_t pad1[23];          // (the claim counters below start a 128-byte line of their own)
+    // window_runs_kernel: next unclaimed piece of each L2 domain, one counter per 128-byte line
+    // (cleared by the kernel's plan kernel)
+    uint32_t win_next[8][32];
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -924,9 +931,10 @@ __global__ __launch_bounds__(kRlThreads) void runlength_write_kernel(
 //     consumed, the sum stays inside the group, and all groups apply their update together;
 //   * longer runs use the whole wavefront (groups take alternate lookups, xor butterfly at the end);
 //     up to kLongRun lookups the owner follows the run past its chunk and finishes it;
-//   * a run longer than kLongRun is cut at chunk borders: every chunk it touches writes one fp32
-//     partial row to the workspace and the run is queued for the fix-up kernel, which adds the
-//     partials in chunk order and applies the single update.
+//   * a run longer than kLongRun is not summed here: it is queued, per table, for window_runs_kernel
+//     (pieces by bag window) or, beyond the call's dense threshold, for dense_rows_kernel (counts x
+//     gradient block); those write fp32 partial rows to the workspace, and the fix-up kernel adds a
+//     run's partial rows in a fixed order and applies the single update.
 // Either way each touched row is read, updated and written exactly once, nothing is accumulated
 // with atomics, and the summation order is fixed: results are bit-identical run to run.
 //
@@ -994,6 +1002,10 @@ struct BwdArgs {
     uint32_t* dense_cnt;   // [T] dense runs queued per table (zero between updates)
     uint32_t* dense_list;  // table t's queue starts at entry tstart[t] / dense_thr + t
     uint32_t* dense_dirty; // [T] set by dense_rows_kernel when a table's gradient block holds Inf / NaN
+    // long runs (kLongRun < length <= dense_thr): queued per table, summed window by window by window_runs_kernel
+    uint32_t* win_cnt;     // [T] (zero between updates)
+    uint32_t* win_list;    // table t's queue starts at entry tstart[t] / kLongRun + t
+    int32_t grad_bytes;    // bytes per gradient element (sizes the bag windows)
     OptParams opt;
 };
 
@@ -1285,15 +1297,9 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     const int q1 = min(a.n, q0 + kChunk);
     const int ub = a.chunk_first_run[k];
     const int ue = a.chunk_first_run[k + 1];
-    const int U = (int)a.counters->num_unique;
     const int nruns = ue - ub;  // runs that start in [q0, q1): at most kChunk
-    if (nruns == 0) {
-        // the chunk lies inside one run; a dense run leaves nothing to do here (dense_rows_kernel sums it)
-        const int sd = a.seg_offsets[ub - 1];
-        const int ed = a.seg_offsets[ub];
-        if (ed - sd > a.dense_thr)
-            return;
-    }
+    if (nruns == 0)
+        return;     // the chunk lies inside one run: its owner, or (long runs) another kernel, sums all of it
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     const int32_t* __restrict__ vals = a.sorted_vals;
     int64_t sumD = a.sumD;   // distance between the gradient rows of consecutive bags (D_t when table-major)
@@ -1350,23 +1356,6 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         }
     };
 
-    // the run that is already open at q0: only its long form leaves work here
-    const bool incoming = (ub >= U) || (a.seg_offsets[ub] > q0);
-    if (incoming) {
-        const int u0 = ub - 1;
-        const int s0 = a.seg_offsets[u0];
-        const int e0 = a.seg_offsets[u0 + 1];
-        if (e0 - s0 > kLongRun && e0 - s0 <= a.dense_thr) {
-            seek_table(a.unique_keys[u0]);
-            const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
-            sumD = a.table_major ? m.dim : a.sumD;
-            const Cols c(m.dim, m.lpr_bwd, lane);
-            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, q0, min(e0, q1),
-                                a.zero_row, c, acc);
-            store_partial(a.partials + ((int64_t)k * 2 + 0) * a.dpad, acc, c);
-        }
-    }
-
     int r = 0;
     while (r < nruns) {
         const uint32_t key0 = (uint32_t)uniform((int)s_key[r]);
@@ -1383,37 +1372,31 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
             // ---- one run, whole wavefront
             const int64_t rel = (int64_t)(key0 - m.rbase) * D;
             WT* wrow = wtab + rel;
-            const bool is_long = len0 > kLongRun;
-            if (len0 > a.dense_thr) {
-                // dense run: queued for dense_rows_kernel (per table) and for the fix-up, nothing is gathered here
+            if (len0 > kLongRun) {
+                // long run: nothing is gathered here.  It is queued for the fix-up kernel and, per table, for the
+                // kernel that sums it: dense_rows_kernel beyond the dense threshold, window_runs_kernel below it
                 if (lane == 0) {
-                    const uint32_t dslot = atomicAdd(&a.dense_cnt[t], 1u);
-                    a.dense_list[a.tstart[t] / a.dense_thr + t + (int)dslot] = (uint32_t)(ub + r);
+                    if (len0 > a.dense_thr) {
+                        const uint32_t dslot = atomicAdd(&a.dense_cnt[t], 1u);
+                        a.dense_list[a.tstart[t] / a.dense_thr + t + (int)dslot] = (uint32_t)(ub + r);
+                    } else {
+                        const uint32_t wslot = atomicAdd(&a.win_cnt[t], 1u);
+                        a.win_list[a.tstart[t] / kLongRun + t + (int)wslot] = (uint32_t)(ub + r);
+                    }
                     const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
-                    a.long_list[slot] = (uint32_t)(ub + r) | 0x80000000u;
+                    a.long_list[slot] = (uint32_t)(ub + r);
                 }
                 r += 1;
                 continue;
             }
             typename IO::Vec wvv[2];
             OptRow<OPT> st;
-            if (!is_long) {
-                wvv[0] = IO::ldv(wrow + c.e0);
-                wvv[1] = IO::ldv(wrow + c.e1);
-                st.load(a.opt, key0, m.woff + rel, c);
-            }
-            const int e = is_long ? q1 : s0 + len0;
-            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, s0, e, a.zero_row, c,
+            wvv[0] = IO::ldv(wrow + c.e0);
+            wvv[1] = IO::ldv(wrow + c.e1);
+            st.load(a.opt, key0, m.woff + rel, c);
+            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, s0, s0 + len0, a.zero_row, c,
                                 acc);
-            if (!is_long) {
-                optimizer_epilogue<WT, OPT>(wrow, wvv, acc, D, c, c.grp == 0, a.opt, key0, m.woff + rel, st);
-            } else {
-                store_partial(a.partials + ((int64_t)k * 2 + 1) * a.dpad, acc, c);
-                if (lane == 0) {
-                    const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
-                    a.long_list[slot] = (uint32_t)(ub + r);
-                }
-            }
+            optimizer_epilogue<WT, OPT>(wrow, wvv, acc, D, c, c.grp == 0, a.opt, key0, m.woff + rel, st);
             r += 1;
         } else {
             // ---- up to G short runs of this table at once, one per lane group
@@ -1470,28 +1453,33 @@ struct DenseGroup {      // 32 bytes
     int32_t pad[3];
 };
 
-struct DenseArgs {
+struct DenseArgs {              // also used for the windowed runs (groups of one run, slices = windows)
     BwdArgs b;
-    const uint32_t* drun;       // compact list of dense runs (run index u), grouped by table
+    const uint32_t* drun;       // compact list of runs (run index u), grouped by table
     const DenseGroup* dgroup;
-    int32_t* dbounds;           // [run][nslices + 1] first sorted position of the run whose bag is >= c * kDenseSlice
-    int32_t nsub;               // number of slices = ceil(batch / kDenseSlice)
+    int32_t* dbounds;           // [run][nsub + 1] first sorted position of the run whose bag is >= c * slice_bags
+    const uint32_t* nruns;      // number of runs in drun (device counter)
+    int32_t nsub;               // number of slices = ceil(batch / slice_bags)
+    int32_t slice_bags;
 };
 
-// one workgroup: per-table queues -> compact run list + groups; clears the per-table counters
-__global__ __launch_bounds__(256) void dense_plan_kernel(BwdArgs a, uint32_t* __restrict__ drun,
-                                                         DenseGroup* __restrict__ dgroup)
+// one workgroup: per-table queues -> compact run list + groups of at most rpg runs; clears the per-table
+// counters.  cnt / list: the queues (table t's starts at entry tstart[t] / base_div + t).
+__global__ __launch_bounds__(256) void run_plan_kernel(BwdArgs a, uint32_t* __restrict__ cnt,
+                                                       const uint32_t* __restrict__ list, int base_div, int rpg,
+                                                       uint32_t* __restrict__ drun, DenseGroup* __restrict__ dgroup,
+                                                       uint32_t* __restrict__ out_runs, uint32_t* __restrict__ out_groups,
+                                                       uint32_t* __restrict__ clear_flags)
 {
     __shared__ uint32_t s_wave[4];
     __shared__ uint32_t s_c[256], s_rfirst[256], s_gfirst[256];
     uint32_t carry_r = 0, carry_g = 0;
     for (int base = 0; base < a.T; base += 256) {
         const int t = base + threadIdx.x;
-        const uint32_t c = t < a.T ? a.dense_cnt[t] : 0u;
-        const uint32_t rpg = (uint32_t)kDenseRows;
+        const uint32_t c = t < a.T ? cnt[t] : 0u;
         const uint32_t g = (c + rpg - 1) / rpg;
-        if (t < a.T)
-            a.dense_dirty[t] = 0;
+        if (t < a.T && clear_flags)
+            clear_flags[t] = 0;
         uint32_t tot_r, tot_g;
         const uint32_t ex_r = block_exclusive_scan_256(c, s_wave, tot_r);
         const uint32_t ex_g = block_exclusive_scan_256(g, s_wave, tot_g);
@@ -1499,25 +1487,41 @@ __global__ __launch_bounds__(256) void dense_plan_kernel(BwdArgs a, uint32_t* __
         s_rfirst[threadIdx.x] = carry_r + ex_r;
         s_gfirst[threadIdx.x] = carry_g + ex_g;
         if (c > 0)
-            a.dense_cnt[t] = 0;
+            cnt[t] = 0;
         __syncthreads();
-        // the whole workgroup copies one table's queue after the other (a queue can be long when the batch is small)
+        // short queues (the usual case) are copied by their own thread, all tables at once ...
+        if (c > 0 && c <= 64) {
+            const uint32_t rfirst = carry_r + ex_r, gfirst = carry_g + ex_g;
+            const uint32_t* q = list + (a.tstart[t] / base_div + t);
+            for (uint32_t i = 0; i < c; ++i)
+                drun[rfirst + i] = q[i];
+            for (uint32_t gi = 0; gi < g; ++gi) {
+                DenseGroup d;
+                d.t = t;
+                d.first = (int32_t)(rfirst + gi * rpg);
+                d.nrows = (int32_t)min((uint32_t)rpg, c - gi * rpg);
+                d.gbase = (int32_t)gfirst;
+                d.ng = (int32_t)g;
+                d.pad[0] = d.pad[1] = d.pad[2] = 0;
+                dgroup[gfirst + gi] = d;
+            }
+        }
+        // ... long ones (a queue can be long when the batch is small) by the whole workgroup, one table after the other
         const int nt = min(256, a.T - base);
         for (int tt = 0; tt < nt; ++tt) {
             const uint32_t ct = s_c[tt];
-            if (ct == 0)
+            if (ct <= 64)
                 continue;
             const uint32_t rfirst = s_rfirst[tt], gfirst = s_gfirst[tt];
-            const uint32_t rpg = (uint32_t)kDenseRows;
             const uint32_t gt = (ct + rpg - 1) / rpg;
-            const uint32_t* q = a.dense_list + (a.tstart[base + tt] / a.dense_thr + base + tt);
+            const uint32_t* q = list + (a.tstart[base + tt] / base_div + base + tt);
             for (uint32_t i = threadIdx.x; i < ct; i += 256)
                 drun[rfirst + i] = q[i];
             for (uint32_t gi = threadIdx.x; gi < gt; gi += 256) {
                 DenseGroup d;
                 d.t = base + tt;
                 d.first = (int32_t)(rfirst + gi * rpg);
-                d.nrows = (int32_t)min(rpg, ct - gi * rpg);
+                d.nrows = (int32_t)min((uint32_t)rpg, ct - gi * rpg);
                 d.gbase = (int32_t)gfirst;
                 d.ng = (int32_t)gt;
                 d.pad[0] = d.pad[1] = d.pad[2] = 0;
@@ -1529,18 +1533,19 @@ __global__ __launch_bounds__(256) void dense_plan_kernel(BwdArgs a, uint32_t* __
         carry_g += tot_g;
     }
     if (threadIdx.x == 0) {
-        a.counters->dense_runs = carry_r;
-        a.counters->dense_groups = carry_g;
+        *out_runs = carry_r;
+        if (out_groups)
+            *out_groups = carry_g;
     }
 }
 
-// one wavefront per dense run: where the run's payloads (ascending bags) cross every multiple of kDenseSlice
-__global__ __launch_bounds__(256) void dense_bounds_kernel(DenseArgs d)
+// one wavefront per listed run: where the run's payloads (ascending bags) cross every multiple of slice_bags
+__global__ __launch_bounds__(256) void run_bounds_kernel(DenseArgs d)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave_global = uniform(blockIdx.x * 4 + (threadIdx.x >> 6));
     const int wave_total = gridDim.x * 4;
-    const int nruns = (int)d.b.counters->dense_runs;
+    const int nruns = (int)*d.nruns;
     const int nb = d.nsub + 1;
     const int32_t* __restrict__ vals = d.b.sorted_vals;
     for (int i = wave_global; i < nruns; i += wave_total) {
@@ -1548,7 +1553,7 @@ __global__ __launch_bounds__(256) void dense_bounds_kernel(DenseArgs d)
         const int s = d.b.seg_offsets[u];
         const int e = d.b.seg_offsets[u + 1];
         for (int c = lane; c < nb; c += kWave) {
-            const int target = c * kDenseSlice;
+            const int target = c * d.slice_bags;
             int lo = s, hi = e;              // first p in [s, e) with vals[p] >= target
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
@@ -1827,9 +1832,235 @@ __global__ __launch_bounds__(kDenseThreads, 4) void dense_rows_kernel(DenseArgs 
     }
 }
 
-// One wavefront per queued long run: adds the per-chunk partial rows in chunk order (first the
-// piece written by the chunk where the run starts, then one piece per following chunk) and applies
-// the run's single AdaGrad step.
+// ---------------------------------------------------------------- long runs, window by window
+//
+// A run of kLongRun < L <= dense threshold lookups is cut into pieces by bag window (the batch is divided
+// into at most kWinMax windows of win_bags bags); the payloads of a run ascend by bag, so a piece is a
+// contiguous part of the run.  One wavefront sums one piece (one gathered gradient row per lookup) and
+// writes one fp32 partial row; the fix-up kernel adds a run's partial rows in window order.  Pieces are
+// processed table by table, window by window, run by run, and the wavefronts that share an L2 work on
+// neighbouring pieces: the gradient rows they gather then come from one window of one table's gradient
+// block (2 MiB for 128 fp32 columns) instead of from all of it, and are mostly found in L2.
+// The partial rows of a run live in the slots of the chunks it covers completely (two per chunk).  A run
+// too short to own kWinMax slots merges neighbouring windows in pairs or fours (8 or 4 pieces).
+
+// Bag windows of a table with D columns: about 2 MiB of its gradient block each (a power of two of at least
+// 1024 bags), at most kWinMax windows per batch.
+struct WinGeom {
+    int bags, nwin;
+};
+
+__device__ __forceinline__ WinGeom window_geom(int batch, int D, int grad_bytes)
+{
+    WinGeom g;
+    g.bags = 1024;
+    while (g.bags * 2 * D * grad_bytes <= (2 << 20))
+        g.bags <<= 1;
+    g.nwin = (batch + g.bags - 1) / g.bags;
+    if (g.nwin > kWinMax) {
+        g.bags = ((batch + kWinMax - 1) / kWinMax + 1023) / 1024 * 1024;
+        g.nwin = (batch + g.bags - 1) / g.bags;
+    }
+    g.nwin = max(g.nwin, 1);
+    return g;
+}
+
+// pieces a run of sorted positions [s, e) is cut into: as many windows as it has slots for, as a power of two
+__device__ __forceinline__ int window_step(int s, int e, int nwin)
+{
+    const int slots = 2 * ((e - 1) / kChunk - s / kChunk - 1);     // >= 6 for a run longer than kLongRun
+    int step = 1;                                                  // windows per piece
+    while ((nwin + step - 1) / step > slots)
+        step <<= 1;
+    return step;
+}
+
+struct WinPiece {        // 16 bytes: what a wavefront needs to sum one piece, in one load
+    int32_t p0, p1;      // sorted positions of the piece
+    int32_t slot;        // partial row it writes; < 0: merged into the piece that starts at an earlier window
+    int32_t t;           // table
+};
+
+// one workgroup: exclusive prefixes of the per-table queue lengths (wpre[T] = number of windowed runs) and of
+// the per-table piece counts, runs x windows (ppre[T] = number of pieces); clears the queue lengths and the
+// piece-claim counters for this update
+__global__ __launch_bounds__(256) void window_plan_kernel(BwdArgs a, uint32_t* __restrict__ wpre,
+                                                          uint32_t* __restrict__ ppre)
+{
+    __shared__ uint32_t s_wave[4];
+    uint32_t carry = 0, carry_p = 0;
+    for (int base = 0; base < a.T; base += 256) {
+        const int t = base + threadIdx.x;
+        const uint32_t c = t < a.T ? a.win_cnt[t] : 0u;
+        const uint32_t np = t < a.T ? c * (uint32_t)window_geom(a.batch, a.meta[t].dim, a.grad_bytes).nwin : 0u;
+        uint32_t tot, tot_p;
+        const uint32_t ex = block_exclusive_scan_256(c, s_wave, tot);
+        const uint32_t ex_p = block_exclusive_scan_256(np, s_wave, tot_p);
+        if (t < a.T) {
+            wpre[t] = carry + ex;
+            ppre[t] = carry_p + ex_p;
+            if (c > 0)
+                a.win_cnt[t] = 0;
+        }
+        carry += tot;
+        carry_p += tot_p;
+    }
+    if (threadIdx.x == 0) {
+        wpre[a.T] = carry;
+        ppre[a.T] = carry_p;
+        a.counters->win_runs = carry;
+        a.counters->win_pieces = carry_p;
+    }
+    if (threadIdx.x < 8)
+        a.counters->win_next[threadIdx.x][0] = 0;
+}
+
+// Sixteen lanes per windowed run (four runs per wavefront): where the run's payloads (ascending bags) cross the
+// window borders, written as the run's piece records.  Run ri belongs to the table t with wpre[t] <= ri <
+// wpre[t + 1] and is entry ri - wpre[t] of that table's queue; the pieces of table t are
+// [ppre[t], ppre[t + 1]), window-major, run-minor.
+__global__ __launch_bounds__(256) void window_pieces_kernel(BwdArgs a, const uint32_t* __restrict__ wpre,
+                                                            const uint32_t* __restrict__ ppre,
+                                                            WinPiece* __restrict__ pieces)
+{
+    static_assert(kWinMax == 16, "one 16-lane group per run");
+    const int lane = threadIdx.x & (kWave - 1);
+    const int sub = lane & 15;
+    const int nruns = (int)wpre[a.T];
+    const int32_t* __restrict__ vals = a.sorted_vals;
+    const int groups_total = gridDim.x * (256 / 16);
+    for (int ri0 = (blockIdx.x * 256 + (int)threadIdx.x) >> 4; ri0 - (ri0 & 3) < nruns; ri0 += groups_total) {
+        const bool live = ri0 < nruns;               // the four groups of a wavefront stay together for the shuffle
+        const int ri = live ? ri0 : nruns - 1;
+        int t0 = 0, t1 = a.T;                        // wpre[t0] <= ri < wpre[t1]
+        while (t1 - t0 > 1) {
+            const int mid = (t0 + t1) >> 1;
+            if ((int)wpre[mid] <= ri)
+                t0 = mid;
+            else
+                t1 = mid;
+        }
+        const int gbase = (int)wpre[t0], ng = (int)wpre[t0 + 1] - gbase;
+        const WinGeom wg = window_geom(a.batch, a.meta[t0].dim, a.grad_bytes);
+        const int nwin = wg.nwin;
+        const int u = (int)a.win_list[a.tstart[t0] / kLongRun + t0 + (ri - gbase)];
+        const int s = a.seg_offsets[u];
+        const int e = a.seg_offsets[u + 1];
+        const int step = window_step(s, e, nwin);
+        int bound = e;                               // first p in [s, e) with vals[p] >= sub * win_bags
+        if (sub < nwin) {
+            const int target = sub * wg.bags;
+            int lo = s, hi = e;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (vals[mid] < target)
+                    lo = mid + 1;
+                else
+                    hi = mid;
+            }
+            bound = lo;
+        }
+        const int up = __shfl(bound, (lane & ~15) | min(sub + step, 15));
+        if (live && sub < nwin) {
+            WinPiece p;
+            p.p0 = bound;
+            p.p1 = sub + step >= nwin ? e : up;
+            p.slot = sub % step == 0 ? (s / kChunk + 1) * 2 + sub / step : -1;
+            p.t = t0;
+            pieces[(int64_t)ppre[t0] + (int64_t)sub * ng + (ri - gbase)] = p;
+        }
+    }
+}
+
+template <typename GT>
+__global__ __launch_bounds__(kBwdThreads) void window_runs_kernel(BwdArgs a, const WinPiece* __restrict__ pieces)
+{
+    using GIO = GradIO<GT>;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int total = (int)a.counters->win_pieces;
+    const GT* __restrict__ grad_out = static_cast<const GT*>(a.grad_out);
+    const GT* zero_row = reinterpret_cast<const GT*>(a.zero_row);
+    const int32_t* __restrict__ vals = a.sorted_vals;
+    // The workgroups that share an L2 (every 8th block) take the pieces of one eighth of the list, kWinBatch
+    // consecutive unclaimed ones at a time (one integer atomic per batch; the wavefronts of the workgroup then
+    // share the batch out through LDS): whatever the pieces' lengths, the wavefronts of an L2 domain are always
+    // at work on neighbouring pieces.  Which wavefront sums a piece has no influence on the result.
+    __shared__ int s_batch, s_taken;
+    const int xcd = blockIdx.x & 7;
+    const int per_xcd = (total + 7) / 8;
+    for (;;) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            s_batch = (int)atomicAdd(&a.counters->win_next[xcd][0], (uint32_t)kWinBatch);
+            s_taken = 0;
+        }
+        __syncthreads();
+        const int batch0 = s_batch;
+        if (batch0 >= per_xcd)
+            break;
+      for (;;) {
+        int w = 0;
+        if (lane == 0)
+            w = atomicAdd(&s_taken, 1);
+        w = uniform(w);
+        if (w >= kWinBatch || batch0 + w >= per_xcd)
+            break;
+        const int piece = xcd * per_xcd + batch0 + w;
+        if (piece >= total)
+            break;
+        const int4 rec = *reinterpret_cast<const int4*>(&pieces[piece]);   // p0, p1, slot, t
+        if (rec.z < 0)
+            continue;                                           // merged into the piece that starts earlier
+        const int p0 = rec.x, p1 = rec.y;
+        const TableMeta m = a.meta[rec.w];
+        const int64_t stride = a.table_major ? m.dim : a.sumD;
+        const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
+        const Cols c(m.dim, m.lpr_bwd, lane);
+        const int G = kWave >> c.lprl;
+        float acc[2][4];
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                acc[k][x] = 0.f;
+        for (int base = p0; base < p1; base += kWave) {
+            const int cnt = min(kWave, p1 - base);
+            const int myv = vals[min(base + lane, p1 - 1)];     // 64 payloads with one coalesced load
+            for (int i0 = 0; i0 < cnt; i0 += G * kBwdUnroll) {
+                typename GIO::Vec v[kBwdUnroll][2];
+                const GT* rp[kBwdUnroll];
+#pragma unroll
+                for (int x = 0; x < kBwdUnroll; ++x) {
+                    const int i = i0 + x * G + c.grp;
+                    const int b = __shfl(myv, min(i, cnt - 1));
+                    rp[x] = i < cnt ? gb + (int64_t)b * stride : zero_row;
+                }
+#pragma unroll
+                for (int x = 0; x < kBwdUnroll; ++x) {
+                    v[x][0] = GIO::ldv(rp[x] + c.e0);
+                    v[x][1] = GIO::ldv(rp[x] + c.e1);
+                }
+#pragma unroll
+                for (int x = 0; x < kBwdUnroll; ++x) {
+                    GIO::add(acc[0], v[x][0]);
+                    GIO::add(acc[1], v[x][1]);
+                }
+            }
+        }
+        for (int sft = 1 << c.lprl; sft < kWave; sft <<= 1) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    acc[k][x] += __shfl_xor(acc[k][x], sft);
+        }
+        store_partial(a.partials + (int64_t)rec.z * a.dpad, acc, c);
+      }
+    }
+}
+
+// One wavefront per queued long run: adds the run's partial rows in order (one per bag slice of a dense
+// run, one per window piece otherwise) and applies the run's single optimizer step.
 template <typename WT, typename GT, int OPT>
 __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
 {
@@ -1841,17 +2072,15 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     float acc[2][4];
     for (int i = wave_global; i < cnt; i += wave_total) {
-        const uint32_t entry = a.long_list[i];
-        const bool dense = (entry & 0x80000000u) != 0u;
-        const int u = (int)(entry & 0x7fffffffu);
+        const int u = (int)a.long_list[i];
         const int s = a.seg_offsets[u];
         const int e = a.seg_offsets[u + 1];
+        const bool dense = e - s > a.dense_thr;
         const uint32_t key = a.unique_keys[u];
         const int t = find_table(a.row_base, a.T, key);
         const TableMeta m = a.meta[t];
         const Cols c(m.dim, m.lpr_bwd, lane);
         const int k0 = s / kChunk;
-        const int k1 = (e - 1) / kChunk;
         const float* pbase = a.partials;
         const int64_t dpad = a.dpad;
         const int64_t wel = m.woff + (int64_t)(key - m.rbase) * m.dim;
@@ -1874,8 +2103,10 @@ __global__ __launch_bounds__(kBwdThreads) void long_run_fixup_kernel(BwdArgs a)
             wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + 1) * 2 + cc) * dpad; }, 0,
                                    a.dense_slices, a.zero_row, c, acc);
         } else {
-            wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + cc) * 2 + (cc == 0 ? 1 : 0)) * dpad; },
-                                   0, k1 - k0 + 1, a.zero_row, c, acc);
+            const int nwin = window_geom(a.batch, m.dim, a.grad_bytes).nwin;
+            const int step = window_step(s, e, nwin);
+            wave_gather_sum<float>([&](int cc) { return pbase + ((int64_t)(k0 + 1) * 2 + cc) * dpad; }, 0,
+                                   (nwin + step - 1) / step, a.zero_row, c, acc);
         }
         optimizer_epilogue<WT, OPT>(wrow, wvv, acc, m.dim, c, c.grp == 0, a.opt, key, wel, st);
     }

@@ -30,9 +30,13 @@ def test_long_runs_add_partial_rows_and_16_bit_types_halve_the_row_bytes():
     # one run of 1280 lookups: a partial fp32 row per 128 positions plus two ragged ends, written and read once
     with_long, _ = bench.kernel_bytes(spec, n_t, u_t, np.array([1280.0]), np.array([1.0]))
     rows = 1280 / 128 + 2
-    # the update kernel writes the partial rows and no longer updates that row itself; the fix-up reads them and does
-    assert with_long["reduce_update"] - base["reduce_update"] == rows * 4 * 64 - (2 * 64 * 4 + 8)
+    # the update kernel no longer gathers that run nor updates its row; window_runs reads its payloads and gradient
+    # rows and writes the partial rows (+ a 16-byte piece record read and written each); the fix-up reads them
+    assert base["reduce_update"] - with_long["reduce_update"] == 1280 * 4 + (2 * 64 * 4 + 8)
+    assert with_long["window_runs"] == 1280 * 4 + min(1280 * 4 * 64, 2048 * 4 * 64) + rows * (4 * 64 + 32)
     assert with_long["long_fixup"] == rows * 4 * 64 + (2 * 64 * 4 + 8)
+    assert bench.window_count(65536, 128, 4) == 16 and bench.window_count(65536, 64, 4) == 8
+    assert bench.window_count(700, 128, 4) == 1 and bench.window_count(1 << 20, 128, 4) == 16
     # the same run beyond the dense threshold: its lookups leave the update kernel; dense_rows reads their payloads
     # and the table's gradient block once and writes one partial row per 1024-bag slice (2 here)
     with_dense, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(1), np.zeros(1), ndense_t=np.array([1280.0]),
