@@ -765,7 +765,7 @@ static tbe_status_t enqueue_update(tbe_s* h, const void* d_grad_out, const OptCa
         a.opt.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)oc.beta2, (double)oc.step)));
     }
     const int per_block = kBwdThreads / kWave;
-    const dim3 grid((unsigned)ceil_div(num_chunks, per_block));
+    const dim3 grid((unsigned)ceil_div(ceil_div(num_chunks, kSpanChunks), per_block));   // a wavefront per span of chunks
     const int64_t max_long = n / kLongRun + 1;
     const dim3 grid_fix((unsigned)std::min<int64_t>(2048, ceil_div(max_long, per_block)));
     if (h->dtype == TBE_DTYPE_FP32)

@@ -239,7 +239,36 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
                 for (int e = 0; e < EPL; ++e)
                     accs[q][k][e] = 0.f;
 
-        if (__ballot(len > 0) != 0ull) {
+        if (__ballot(len > 0) != 0ull && LPR >= kFwdUnroll) {
+            // The address unit spends as long on a 4-byte load as on a 16-byte one, so the indices are not
+            // loaded once per row: the LPR lanes of a group load the bag's next LPR indices with ONE
+            // instruction (lane `sub` the sub-th of them) a block ahead of their use, and every row load
+            // takes its index from the group's lanes by a shuffle.
+            const int gbase = lane & ~(LPR - 1);
+            int cur = 0;
+            int nxt = indices[min((uint32_t)(start + sub), last)];
+            for (int it = 0; __ballot(it < len) != 0ull; it += kFwdUnroll) {
+                if ((it & (LPR - 1)) == 0) {
+                    cur = nxt;
+                    nxt = indices[min((uint32_t)(start + it + LPR + sub), last)];
+                }
+                Vec raw[kFwdUnroll][KMAX];
+#pragma unroll
+                for (int u = 0; u < kFwdUnroll; ++u) {
+                    const int idx = __shfl(cur, gbase | ((it + u) & (LPR - 1)));
+                    const WT* rp = (it + u < len) ? wbase + (int64_t)idx * D : zrow;
+#pragma unroll
+                    for (int k = 0; k < KMAX; ++k)
+                        raw[u][k] = IO::ldv(rp + eoff[k]);
+                }
+#pragma unroll
+                for (int u = 0; u < kFwdUnroll; ++u)
+#pragma unroll
+                    for (int k = 0; k < KMAX; ++k)
+                        IO::add(accs[u % NACC][k], raw[u][k]);
+            }
+        } else if (__ballot(len > 0) != 0ull) {
+            // rows of one or two lanes: every lane loads its own indices
             int idx[kFwdUnroll];
 #pragma unroll
             for (int u = 0; u < kFwdUnroll; ++u)
@@ -922,19 +951,25 @@ __global__ __launch_bounds__(kRlThreads) void runlength_write_kernel(
 // Section 5.1: all gradients of one row are aggregated on chip and the optimizer runs once per row.
 // Section 5.2: m += mean_d(G_d^2); w -= lr * G / (sqrt(m) + eps)  (updated moment, eps outside the root).
 //
-// Each wavefront owns kChunk consecutive sorted positions and every run that STARTS inside them.
-// The chunk's run descriptors and payloads are staged in LDS once.  Lane mapping: a row of D floats
+// Each wavefront owns a span of kSpan consecutive sorted positions and every run that STARTS inside it.
+// The span's run descriptors and payloads are staged in LDS once.  Lane mapping: a row of D floats
 // is covered by LPR = pow2ceil(D/8) lanes, two float4 blocks per lane, so G = 64/LPR rows are
-// fetched per load instruction.
-//   * runs of at most kShortRun lookups (the vast majority) are handled G at a time, one per lane
-//     group: all their gradient rows, weight rows and moments are requested before anything is
-//     consumed, the sum stays inside the group, and all groups apply their update together;
-//   * longer runs use the whole wavefront (groups take alternate lookups, xor butterfly at the end);
-//     up to kLongRun lookups the owner follows the run past its chunk and finishes it;
+// fetched per load instruction.  The runs of the span are sorted by length class (a counting sort with
+// ballots into a byte list in LDS) and handled class by class, so that every step is full:
+//   * runs of one or two lookups: several per lane group and step (as many as the registers hold);
+//   * runs of up to kShortRun lookups: one per lane group; all gradient rows, weight rows and moments
+//     of a step are requested before anything is consumed, and all groups apply their update together;
+//   * runs of up to 4 x 2^j lookups, 2^j <= G: teams of 2^j lane groups, G / 2^j runs per step, the
+//     members' sums combined with an xor butterfly;
+//   * longer runs use the whole wavefront in several steps (groups take alternate lookups); up to
+//     kLongRun lookups the owner follows the run past its span and finishes it;
 //   * a run longer than kLongRun is not summed here: it is queued, per table, for window_runs_kernel
 //     (pieces by bag window) or, beyond the call's dense threshold, for dense_rows_kernel (counts x
 //     gradient block); those write fp32 partial rows to the workspace, and the fix-up kernel adds a
 //     run's partial rows in a fixed order and applies the single update.
+// The single-lookup rows of the tail of the index distribution move a row, its moment and one gradient row
+// each and run at the rate of the memory system; the steps of the longer runs are bound by how fast gradient
+// rows come out of the caches, so nothing here is arranged around instruction counts.
 // Either way each touched row is read, updated and written exactly once, nothing is accumulated
 // with atomics, and the summation order is fixed: results are bit-identical run to run.
 //
@@ -1227,48 +1262,99 @@ __device__ __forceinline__ void store_partial(float* __restrict__ dst, const flo
     }
 }
 
-// G short runs at once, one per lane group; ML = longest run of the batch (1..kShortRun).
-template <typename WT, typename GT, int OPT, int ML>
-__device__ __forceinline__ void short_batch(const BwdArgs& a, WT* __restrict__ wtab, int64_t woff,
-                                            const GT* __restrict__ gb, int64_t sumD,
-                                            const int32_t* __restrict__ s_val, int q0,
-                                            int s, int len, uint32_t key, uint32_t rbase, int D, const Cols& c,
-                                            bool active)
+// One step of the update kernel: up to NB * (G >> tsl) runs of one table at once.  The G lane groups of the
+// wavefront form teams of 1 << tsl groups; a team takes NB runs from the class list (entries i0 .. i0 + cnt - 1,
+// run indices of the wavefront's span), every member group fetches up to ML gradient rows of each (member m takes
+// the lookups m, m + team size, ...), the members' sums are combined with an xor butterfly, and member 0 applies
+// the update.  All weight rows, moments and gradient rows of the step are requested before anything is consumed:
+// the number of rows in flight per wavefront, not the instruction count, bounds this kernel.
+template <typename WT, typename GT, int OPT, int ML, int NB>
+__device__ __forceinline__ void run_batch(const BwdArgs& a, WT* __restrict__ wtab, int64_t woff,
+                                          const GT* __restrict__ gb, int sumD,
+                                          const int32_t* __restrict__ s_seg, const uint32_t* __restrict__ s_key,
+                                          const int32_t* __restrict__ s_val, const uint8_t* __restrict__ s_list,
+                                          int q0, int i0, int cnt, int tsl, uint32_t rbase, int D, const Cols& c)
 {
     using IO = RowIO<WT, 4>;
     using GIO = GradIO<GT>;
-    const int64_t rel = (int64_t)(key - rbase) * D;        // key is a valid row even for idle groups
-    WT* wrow = wtab + rel;
-    typename IO::Vec wv[2];
-    wv[0] = IO::ldv(wrow + c.e0);
-    wv[1] = IO::ldv(wrow + c.e1);
-    OptRow<OPT> st;
-    st.load(a.opt, key, woff + rel, c);
-    const GT* rp[ML];
+    const int teams = (kWave >> c.lprl) >> tsl;
+    const int team = c.grp >> tsl;
+    const int member = c.grp & ((1 << tsl) - 1);
+    typename IO::Vec wv[NB][2];
+    OptRow<OPT> st[NB];
+    uint32_t key[NB];
+    int vbase[NB], len[NB], run[NB];
+    bool act[NB];
+    // all LDS reads of a level are issued together: the row requests below start one LDS round trip
+    // after the other, not one per run
 #pragma unroll
-    for (int u = 0; u < ML; ++u) {
-        const int b = s_val[s - q0 + (u < len ? u : 0)];
-        rp[u] = (active && u < len) ? gb + (int64_t)b * sumD : reinterpret_cast<const GT*>(a.zero_row);
+    for (int j = 0; j < NB; ++j) {
+        const int li = j * teams + team;
+        act[j] = li < cnt;
+        run[j] = s_list[i0 + (act[j] ? li : 0)];     // idle teams shadow the first run: loads stay valid
     }
-    typename GIO::Vec v[ML][2];
 #pragma unroll
-    for (int u = 0; u < ML; ++u) {
-        v[u][0] = GIO::ldv(rp[u] + c.e0);
-        v[u][1] = GIO::ldv(rp[u] + c.e1);
+    for (int j = 0; j < NB; ++j) {
+        key[j] = s_key[run[j]];
+        vbase[j] = s_seg[run[j]];
+        len[j] = s_seg[run[j] + 1];
     }
-    float acc[2][4];
 #pragma unroll
-    for (int k = 0; k < 2; ++k)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            acc[k][e] = 0.f;
-#pragma unroll
-    for (int u = 0; u < ML; ++u) {
-        GIO::add(acc[0], v[u][0]);
-        GIO::add(acc[1], v[u][1]);
+    for (int j = 0; j < NB; ++j) {
+        len[j] = act[j] ? len[j] - vbase[j] : 0;
+        vbase[j] -= q0;
+        const uint64_t rel = (uint64_t)(key[j] - rbase) * (uint32_t)D;
+        wv[j][0] = IO::ldv(wtab + rel + c.e0);
+        wv[j][1] = IO::ldv(wtab + rel + c.e1);
+        st[j].load(a.opt, key[j], woff + (int64_t)rel, c);
     }
-    optimizer_epilogue<WT, OPT>(wrow, wv, acc, D, c, active, a.opt, key, woff + rel, st);
+    typename GIO::Vec v[NB][ML][2];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const GT* rp[ML];
+#pragma unroll
+        for (int u = 0; u < ML; ++u) {
+            const int pos = member + (u << tsl);
+            const bool ok = pos < len[j];
+            const int b = s_val[vbase[j] + (ok ? pos : 0)];
+            rp[u] = ok ? gb + (uint64_t)(uint32_t)b * (uint32_t)sumD : reinterpret_cast<const GT*>(a.zero_row);
+        }
+#pragma unroll
+        for (int u = 0; u < ML; ++u) {
+            v[j][u][0] = GIO::ldv(rp[u] + c.e0);
+            v[j][u][1] = GIO::ldv(rp[u] + c.e1);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        float acc[2][4];
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                acc[k][e] = 0.f;
+#pragma unroll
+        for (int u = 0; u < ML; ++u) {
+            GIO::add(acc[0], v[j][u][0]);
+            GIO::add(acc[1], v[j][u][1]);
+        }
+        for (int sh = 1 << c.lprl; sh < (1 << (c.lprl + tsl)); sh <<= 1) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc[k][e] += __shfl_xor(acc[k][e], sh);
+        }
+        uint32_t kj = key[j];
+        asm volatile("" : "+v"(kj));    // the store addresses are formed again here, not kept in registers meanwhile
+        const uint64_t rel = (uint64_t)(kj - rbase) * (uint32_t)D;
+        optimizer_epilogue<WT, OPT>(wtab + rel, wv[j], acc, D, c, act[j] && member == 0, a.opt, kj,
+                                    woff + (int64_t)rel, st[j]);
+    }
 }
+
+constexpr int kSpanChunks = 2;                  // chunks owned by one wavefront of the update kernel
+constexpr int kSpan = kSpanChunks * kChunk;     // 256 sorted positions
 
 template <typename WT, typename GT, int OPT>
 __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
@@ -1276,65 +1362,74 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     using IO = RowIO<WT, 4>;
     const GT* __restrict__ grad_out = static_cast<const GT*>(a.grad_out);
     constexpr int kWaves = kBwdThreads / kWave;
-    constexpr int kSegCap = 3 * kWave;             // >= kChunk + 1
-    constexpr int kValCap = kChunk + kLongRun;     // a run owned by the chunk ends within this window
+    constexpr int kRounds = kSpan / kWave;         // staging rounds of one entry per lane
+    constexpr int kSegCap = (kRounds + 1) * kWave; // >= kSpan + 1
+    constexpr int kValCap = kSpan + kLongRun;      // a run owned by the span ends within this window
+    // row-wise AdaGrad keeps one moment per row, so several runs per lane group fit in registers; the
+    // element-wise optimizers carry whole state rows and take one run per group
+    constexpr int kNB1 = OPT != kOptRowwiseAdagrad ? 1 : sizeof(WT) == 2 ? 4 : 2;   // runs of one lookup per group
+    constexpr int kNB2 = OPT != kOptRowwiseAdagrad ? 1 : 2;                          // runs of two lookups per group
     static_assert(kFwdUnroll == 4, "the forward adds its four accumulators pairwise");
-    static_assert(kChunk + 1 <= kSegCap && kChunk == 2 * kWave, "staging loops assume a 128-position chunk");
+    static_assert(kSpan <= 256, "run indices of a span are kept in bytes");
+    static_assert(kShortRun == 4, "run_batch is instantiated for 1..4 lookups");
     __shared__ int32_t s_seg_all[kWaves][kSegCap];
-    __shared__ uint32_t s_key_all[kWaves][kChunk];
+    __shared__ uint32_t s_key_all[kWaves][kSpan];
     __shared__ int32_t s_val_all[kWaves][kValCap];
+    __shared__ uint8_t s_list_all[kWaves][kSpan];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x >> 6;
     const int k = uniform(blockIdx.x * kWaves + wv);
-    if (k >= a.num_chunks)
+    const int ch0 = k * kSpanChunks;
+    if (ch0 >= a.num_chunks)
         return;
+    const int ch1 = min(ch0 + kSpanChunks, a.num_chunks);
     int32_t* s_seg = s_seg_all[wv];
     uint32_t* s_key = s_key_all[wv];
     int32_t* s_val = s_val_all[wv];
+    uint8_t* s_list = s_list_all[wv];
 
-    const int q0 = k * kChunk;
-    const int q1 = min(a.n, q0 + kChunk);
-    const int ub = a.chunk_first_run[k];
-    const int ue = a.chunk_first_run[k + 1];
-    const int nruns = ue - ub;  // runs that start in [q0, q1): at most kChunk
+    const int q0 = ch0 * kChunk;
+    const int q1 = min(a.n, q0 + kSpan);
+    const int ub = a.chunk_first_run[ch0];
+    const int ue = a.chunk_first_run[ch1];
+    const int nruns = ue - ub;  // runs that start in [q0, q1): at most kSpan
     if (nruns == 0)
-        return;     // the chunk lies inside one run: its owner, or (long runs) another kernel, sums all of it
+        return;     // the span lies inside one run: its owner, or (long runs) another kernel, sums all of it
     WT* __restrict__ weights = static_cast<WT*>(a.weights);
     const int32_t* __restrict__ vals = a.sorted_vals;
-    int64_t sumD = a.sumD;   // distance between the gradient rows of consecutive bags (D_t when table-major)
 
     // ---- stage run descriptors and payloads (wavefront-private LDS); straight-line clamped loads
     {
-        int sg[3];
-        uint32_t ky[2];
-        int vl[2];
+        int sg[kRounds + 1];
+        uint32_t ky[kRounds];
+        int vl[kRounds];
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
+        for (int i = 0; i < kRounds + 1; ++i)
             sg[i] = a.seg_offsets[ub + min(i * kWave + lane, nruns)];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            ky[i] = a.unique_keys[ub + min(i * kWave + lane, max(nruns - 1, 0))];
+        for (int i = 0; i < kRounds; ++i)
+            ky[i] = a.unique_keys[ub + min(i * kWave + lane, nruns - 1)];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < kRounds; ++i)
             vl[i] = vals[min(q0 + i * kWave + lane, a.n - 1)];
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
+        for (int i = 0; i < kRounds + 1; ++i)
             s_seg[i * kWave + lane] = sg[i];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < kRounds; ++i) {
             s_key[i * kWave + lane] = ky[i];
             s_val[i * kWave + lane] = vl[i];
         }
     }
     __threadfence_block();
     __builtin_amdgcn_wave_barrier();
-    // the last run that starts here may continue past the chunk: stage its payloads too, unless it is
-    // a long run (then only its part inside the chunk is summed here)
+    // the last run that starts here may continue past the span: stage its payloads too, unless it is
+    // a long run (those are not summed here)
     {
         const int e_last = uniform(s_seg[nruns]);
-        const int s_last = uniform(s_seg[max(nruns - 1, 0)]);
-        if (nruns > 0 && e_last > q1 && e_last - s_last <= kLongRun) {
+        const int s_last = uniform(s_seg[nruns - 1]);
+        if (e_last > q1 && e_last - s_last <= kLongRun) {
             for (int p = q1 + lane; p < e_last; p += kWave)
                 s_val[p - q0] = vals[p];
             __threadfence_block();
@@ -1342,89 +1437,169 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
         }
     }
 
-    float acc[2][4];
-    int t = -1;
-    uint32_t t_lo = 1u, t_hi = 0u;  // empty range: the first key always seeks
-    TableMeta m;
-    m.woff = 0; m.rbase = 0; m.dim = 4; m.col = 0; m.lpr_fwd = 0; m.lpr_bwd = 0; m.key_bits = 1;
-    auto seek_table = [&](uint32_t key) {
-        if (key < t_lo || key >= t_hi) {
-            t = find_table(a.row_base, a.T, key);
-            m = a.meta[t];
-            t_lo = a.row_base[t];
-            t_hi = a.row_base[t + 1];
+    const uint64_t lt = (1ull << lane) - 1ull;
+    // entries [0, count) of s_list <- the span's runs of class cl, in run order
+    auto build_list = [&](const int (&cls)[kRounds], int cl, int first) {
+        int n = first;
+#pragma unroll
+        for (int i = 0; i < kRounds; ++i) {
+            const uint64_t mk = __ballot(cls[i] == cl);
+            if (cls[i] == cl)
+                s_list[n + __popcll(mk & lt)] = (uint8_t)(i * kWave + lane);
+            n += __popcll(mk);
         }
+        return n;
+    };
+    auto run_len = [&](int li) {
+        const int run = s_list[li];
+        return uniform(s_seg[run + 1] - s_seg[run]);
     };
 
-    int r = 0;
-    while (r < nruns) {
-        const uint32_t key0 = (uint32_t)uniform((int)s_key[r]);
-        seek_table(key0);
+    int ra = 0;
+    while (ra < nruns) {
+        // ---- the runs [ra, rb) of the table of run ra (a span rarely touches more than one table)
+        const uint32_t key0 = (uint32_t)uniform((int)s_key[ra]);
+        const int t = uniform(find_table(a.row_base, a.T, key0));
+        TableMeta m = a.meta[t];            // wavefront-uniform: kept in scalar registers
+        m.woff = ((int64_t)uniform((int)(m.woff >> 32)) << 32) | (uint32_t)uniform((int)m.woff);
+        m.rbase = (uint32_t)uniform((int)m.rbase);
+        m.dim = uniform(m.dim);
+        m.col = uniform(m.col);
+        m.lpr_bwd = uniform(m.lpr_bwd);
+        const uint32_t t_hi = (uint32_t)uniform((int)a.row_base[t + 1]);
+        int rb = 0;
+#pragma unroll
+        for (int i = 0; i < kRounds; ++i) {
+            const int run = i * kWave + lane;
+            rb += __popcll(__ballot(run < nruns && s_key[min(run, nruns - 1)] < t_hi));
+        }
         const int D = m.dim;
         const int lprl = m.lpr_bwd;
-        const int s0 = uniform(s_seg[r]);
-        const int len0 = uniform(s_seg[r + 1]) - s0;
+        const int lgG = 6 - lprl;
+        const int G = 1 << lgG;
         const GT* gb = a.table_major ? grad_out + (int64_t)a.batch * m.col : grad_out + m.col;
-        sumD = a.table_major ? m.dim : a.sumD;
+        const int sumD = a.table_major ? m.dim : (int)a.sumD;   // distance between the gradient rows of consecutive bags
         WT* wtab = weights + m.woff;
         const Cols c(D, lprl, lane);
-        if (len0 > kShortRun) {
-            // ---- one run, whole wavefront
-            const int64_t rel = (int64_t)(key0 - m.rbase) * D;
-            WT* wrow = wtab + rel;
-            if (len0 > kLongRun) {
-                // long run: nothing is gathered here.  It is queued for the fix-up kernel and, per table, for the
-                // kernel that sums it: dense_rows_kernel beyond the dense threshold, window_runs_kernel below it
-                if (lane == 0) {
-                    if (len0 > a.dense_thr) {
-                        const uint32_t dslot = atomicAdd(&a.dense_cnt[t], 1u);
-                        a.dense_list[a.tstart[t] / a.dense_thr + t + (int)dslot] = (uint32_t)(ub + r);
-                    } else {
-                        const uint32_t wslot = atomicAdd(&a.win_cnt[t], 1u);
-                        a.win_list[a.tstart[t] / kLongRun + t + (int)wslot] = (uint32_t)(ub + r);
-                    }
-                    const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
-                    a.long_list[slot] = (uint32_t)(ub + r);
+
+        // ---- classes by length: 0 .. 3: one .. four lookups; 3 + j: up to 4 << j lookups, summed by a team of
+        // 1 << j lane groups (while that is at most a wavefront); 14: whole wavefront, several steps;
+        // 15: long, queued for the fix-up kernel and, per table, for the kernel that sums it
+        int cls[kRounds];
+#pragma unroll
+        for (int i = 0; i < kRounds; ++i) {
+            const int run = i * kWave + lane;
+            const bool valid = run >= ra && run < rb;
+            const int rc = valid ? run : ra;
+            const int len = s_seg[rc + 1] - s_seg[rc];
+            int cl;
+            if (len <= kShortRun) {
+                cl = len - 1;
+            } else if (len > kLongRun) {
+                cl = 15;
+            } else {
+                const int tl = 32 - __clz((len - 1) >> 2);     // smallest tl with (4 << tl) >= len
+                cl = tl <= lgG ? 3 + tl : 14;
+            }
+            cls[i] = valid ? cl : -1;
+            if (valid && cl == 15) {
+                if (len > a.dense_thr) {
+                    const uint32_t dslot = atomicAdd(&a.dense_cnt[t], 1u);
+                    a.dense_list[a.tstart[t] / a.dense_thr + t + (int)dslot] = (uint32_t)(ub + run);
+                } else {
+                    const uint32_t wslot = atomicAdd(&a.win_cnt[t], 1u);
+                    a.win_list[a.tstart[t] / kLongRun + t + (int)wslot] = (uint32_t)(ub + run);
                 }
-                r += 1;
-                continue;
+                const uint32_t slot = atomicAdd(&a.counters->long_count, 1u);
+                a.long_list[slot] = (uint32_t)(ub + run);
             }
-            typename IO::Vec wvv[2];
-            OptRow<OPT> st;
-            wvv[0] = IO::ldv(wrow + c.e0);
-            wvv[1] = IO::ldv(wrow + c.e1);
-            st.load(a.opt, key0, m.woff + rel, c);
-            wave_gather_sum<GT>([&](int i) { return gb + (int64_t)s_val[i - q0] * sumD; }, s0, s0 + len0, a.zero_row, c,
-                                acc);
-            optimizer_epilogue<WT, OPT>(wrow, wvv, acc, D, c, c.grp == 0, a.opt, key0, m.woff + rel, st);
-            r += 1;
-        } else {
-            // ---- up to G short runs of this table at once, one per lane group
-            const int rr = r + c.grp;
-            const bool in_chunk = rr < nruns;
-            const int rc = in_chunk ? rr : r;  // idle groups shadow run r (loads stay valid, nothing is stored)
-            const uint32_t key = s_key[rc];
-            const int s = s_seg[rc];
-            const int len = s_seg[rc + 1] - s;
-            const bool fits = in_chunk && key < t_hi && len <= kShortRun;
-            const uint64_t bad = __ballot(!fits);
-            const int first_bad = bad ? (int)__builtin_ctzll(bad) : kWave;
-            const int nb = first_bad >> lprl;  // >= 1: run r itself fits
-            const bool active = c.grp < nb;
-            const uint32_t keyc = active ? key : key0;
-            const int sc = active ? s : s0;
-            const int lenc = active ? len : 0;
-            const int ml = 1 + (__ballot(lenc > 1) != 0ull) + (__ballot(lenc > 2) != 0ull) +
-                           (__ballot(lenc > 3) != 0ull);
-            static_assert(kShortRun == 4, "short_batch is instantiated for 1..4 lookups");
-            switch (ml) {
-                case 1: short_batch<WT, GT, OPT, 1>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                case 2: short_batch<WT, GT, OPT, 2>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                case 3: short_batch<WT, GT, OPT, 3>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-                default: short_batch<WT, GT, OPT, 4>(a, wtab, m.woff, gb, sumD, s_val, q0, sc, lenc, keyc, m.rbase, D, c, active); break;
-            }
-            r += nb;
         }
+
+        // ---- runs of up to four lookups, shortest first: as many per step as the registers hold
+        {
+            int nshort = build_list(cls, 0, 0);
+            nshort = build_list(cls, 1, nshort);
+            nshort = build_list(cls, 2, nshort);
+            nshort = build_list(cls, 3, nshort);
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+            int i = 0;
+            while (i < nshort) {
+                const int rem = nshort - i;
+                if (kNB1 > 1 && rem > G) {
+                    const int cand = min(kNB1 * G, rem);
+                    if (run_len(i + cand - 1) == 1) {
+                        if (kNB1 > 2 && cand > 2 * G)
+                            run_batch<WT, GT, OPT, 1, kNB1>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c);
+                        else
+                            run_batch<WT, GT, OPT, 1, 2>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c);
+                        i += cand;
+                        continue;
+                    }
+                }
+                if (kNB2 > 1 && rem > G) {
+                    const int cand = min(2 * G, rem);
+                    const int ml = run_len(i + cand - 1);
+                    if (ml <= 2) {
+                        if (ml == 1)
+                            run_batch<WT, GT, OPT, 1, 2>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c);
+                        else
+                            run_batch<WT, GT, OPT, 2, 2>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c);
+                        i += cand;
+                        continue;
+                    }
+                }
+                const int cand = min(G, rem);
+                switch (run_len(i + cand - 1)) {
+                    case 1: run_batch<WT, GT, OPT, 1, 1>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c); break;
+                    case 2: run_batch<WT, GT, OPT, 2, 1>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c); break;
+                    case 3: run_batch<WT, GT, OPT, 3, 1>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c); break;
+                    default: run_batch<WT, GT, OPT, 4, 1>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, cand, 0, m.rbase, D, c); break;
+                }
+                i += cand;
+            }
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- teams of 2, 4, ... lane groups: runs of up to 4 lookups per member group, one step each
+        for (int tl = 1; tl <= lgG; ++tl) {
+            const int cnt = build_list(cls, 3 + tl, 0);
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+            const int teams = G >> tl;
+            for (int i = 0; i < cnt; i += teams)
+                run_batch<WT, GT, OPT, 4, 1>(a, wtab, m.woff, gb, sumD, s_seg, s_key, s_val, s_list, q0, i, min(teams, cnt - i), tl, m.rbase, D, c);
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- longer runs: the whole wavefront, several steps
+        {
+            const int cnt = build_list(cls, 14, 0);
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+            for (int i = 0; i < cnt; ++i) {
+                const int run = uniform((int)s_list[i]);
+                const uint32_t key = (uint32_t)uniform((int)s_key[run]);
+                const int s0 = uniform(s_seg[run]);
+                const int len0 = uniform(s_seg[run + 1]) - s0;
+                const int64_t rel = (int64_t)(key - m.rbase) * D;
+                WT* wrow = wtab + rel;
+                typename IO::Vec wvv[2];
+                OptRow<OPT> st;
+                wvv[0] = IO::ldv(wrow + c.e0);
+                wvv[1] = IO::ldv(wrow + c.e1);
+                st.load(a.opt, key, m.woff + rel, c);
+                float acc[2][4];
+                wave_gather_sum<GT>([&](int p) { return gb + (int64_t)s_val[p - q0] * sumD; }, s0, s0 + len0, a.zero_row,
+                                    c, acc);
+                optimizer_epilogue<WT, OPT>(wrow, wvv, acc, D, c, c.grp == 0, a.opt, key, m.woff + rel, st);
+            }
+            __threadfence_block();
+            __builtin_amdgcn_wave_barrier();
+        }
+        ra = rb;
     }
 }
 

@@ -38,10 +38,14 @@ def _touched(spec, art):
     return elem
 
 
-def _run(spec, optimizer, grad_dtype, device, steps=2, seed=0):
-    b = wl.make_batch(spec, "cpu", seed=seed + 1)
-    idx, off = b.indices.numpy(), b.offsets.numpy()
-    N, B = b.num_indices, spec.batch
+def _run(spec, optimizer, grad_dtype, device, steps=2, seed=0, batch=None):
+    """batch: (indices, offsets) as numpy arrays; drawn from the spec's recipe when None."""
+    if batch is None:
+        b = wl.make_batch(spec, "cpu", seed=seed + 1)
+        idx, off = b.indices.numpy(), b.offsets.numpy()
+    else:
+        idx, off = batch
+    N, B = int(idx.size), spec.batch
     w0 = wl.make_weights(spec, "cpu", seed=seed + 2).numpy()
     rtol_w = tl.rtol_for(spec.dtype)
     op = tbe.TableBatchedEmbeddingBags(spec.rows, spec.dims, spec.dtype, B, max(N, 1), device=device,
