@@ -389,9 +389,9 @@ def bench_inputs(args, spec, dev):
 
 
 def stream_rates(dev):
-    """What plain streaming kernels reach on this machine (torch's own kernels over 1 GiB of float32): a device
-    copy (read + write), a read-only reduction and a write-only fill.  Second denominators beside the
-    published peak."""
+    """What plain streaming kernels reach on this machine over 1 GiB of float32: torch's device copy (read + write),
+    its read-only reduction and its write-only fill, and the library's read probe.  Second denominators beside
+    the published peak."""
     import torch
 
     n = 1 << 28
@@ -412,6 +412,18 @@ def stream_rates(dev):
     r = {"copy_GBps": rate(lambda: dst.copy_(src), 8.0 * n),
          "read_only_GBps": rate(lambda: src.sum(), 4.0 * n),
          "write_only_GBps": rate(lambda: dst.fill_(2.0), 4.0 * n)}
+    # the library's own read probe (coalesced 16-byte loads, nothing else): over the 1 GiB buffer (HBM) and over
+    # its first 128 MiB read 8 times per launch (resident in the memory-side cache after the first pass)
+    from paper_2104_05158_amd import tbe as _tbe
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def probe(nbytes, passes):
+        st = _tbe.tbe_probe_read(src, nbytes, passes, sink)
+        if st != 0:
+            raise RuntimeError(f"tbe_probe_read: status {st}")
+
+    r["read_probe_GBps"] = rate(lambda: probe(4 * n, 4), 16.0 * n, reps=4)
+    r["read_probe_cache_resident_GBps"] = rate(lambda: probe(128 << 20, 8), 8.0 * (128 << 20))
     del src, dst
     return r
 
@@ -771,6 +783,10 @@ def main():
     if rates:
         result["roofline"].update(rates)
         result["roofline"]["frac_of_copy"] = round(result["roofline"]["achieved"] / rates["copy_GBps"], 4)
+        if result["roofline"].get("traffic_GBps"):
+            # the dominant kernel's L2<->fabric rate against what plain coalesced reads reach on this machine
+            result["roofline"]["traffic_rate_over_read_probe"] = round(
+                result["roofline"]["traffic_GBps"] / rates["read_probe_GBps"], 4)
     extra = []
     for k in others:
         r = run_workload(args, wl.config(k), dev, headline=False)

@@ -246,6 +246,16 @@ TBE_API tbe_status_t tbe_profile_enable(tbe_handle_t h, int32_t max_calls);
 TBE_API tbe_status_t tbe_profile_read(tbe_handle_t h, int32_t capacity, const char** names,
                               int64_t* launches, double* total_ms, int32_t* num_slots);
 
+/*
+ * Measurement aid (Appendix A measures its kernels against the bandwidth the machine reaches): enqueues one
+ * kernel that reads the first bytes / 16 * 16 bytes of d_src `passes` times with coalesced 16-byte loads and
+ * discards them.  d_src: device memory, 16-byte aligned, at least 16 bytes; d_sink: 4 bytes of device memory
+ * (practically never written); both stay the caller's.  Timed by the caller (events on `stream`): bytes x
+ * passes / duration is the read rate of the memory level the buffer fits in.  No handle, no allocation.
+ * Errors: TBE_ERR_INVALID_ARG (null or misaligned pointer, bytes < 16, passes < 1), TBE_ERR_HIP.
+ */
+TBE_API tbe_status_t tbe_probe_read(const void* d_src, size_t bytes, int32_t passes, void* d_sink, void* stream);
+
 TBE_API const char* tbe_status_string(tbe_status_t s);
 
 /* Text of the last HIP error seen by this handle ("" if none); valid until the next call. */

@@ -967,4 +967,16 @@ tbe_status_t tbe_profile_read(tbe_handle_t h, int32_t capacity, const char** nam
     return TBE_OK;
 }
 
+tbe_status_t tbe_probe_read(const void* d_src, size_t bytes, int32_t passes, void* d_sink, void* stream)
+{
+    if (!d_src || !d_sink || bytes < 16 || passes < 1 || (reinterpret_cast<uintptr_t>(d_src) & 15u) != 0 ||
+        (reinterpret_cast<uintptr_t>(d_sink) & 3u) != 0)
+        return TBE_ERR_INVALID_ARG;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>(8192, (n16 + 255) / 256);
+    hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(d_src), n16, (int)passes, static_cast<uint32_t*>(d_sink));
+    return hipGetLastError() == hipSuccess ? TBE_OK : TBE_ERR_HIP;
+}
+
 }  // extern "C"

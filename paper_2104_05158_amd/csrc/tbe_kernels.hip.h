@@ -150,6 +150,35 @@ struct RowIO<__half, 8> {
     }
 };
 
+// ---------------------------------------------------------------- read-rate probe
+//
+// Streams n16 16-byte words through the chip `passes` times and discards them: the denominator for the
+// gather kernels (what plain coalesced reads reach on the machine at hand, from HBM or, for a buffer that fits
+// the memory-side cache, from there).  Four loads in flight per thread; an opaque copy of the pointer per pass
+// keeps the passes from being merged; the sink is written only for one xor value in 2^32 (a vector store).
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4* p, size_t n16, int passes, uint32_t* sink)
+{
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (int ps = 0; ps < passes; ++ps) {
+        // every pass gives a workgroup another part of the buffer (and another L2): a buffer larger than the
+        // L2s is read from the level behind them in every pass, not from the workgroup's own lines
+        const unsigned vb = (blockIdx.x + (unsigned)ps * 2731u) % gridDim.x;
+        size_t i = (size_t)vb * 256 + threadIdx.x;
+        for (; i + 3 * stride < n16; i += 4 * stride) {
+            const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+            acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+        }
+        for (; i < n16; i += stride) {
+            const uint4 a = p[i];
+            acc ^= a.x ^ a.y ^ a.z ^ a.w;
+        }
+        asm volatile("" : "+s"(p)::"memory");      // the next pass reads through a pointer the compiler cannot relate to this one
+    }
+    if (acc == 0x9e3779b9u)
+        *sink = acc;
+}
+
 // ---------------------------------------------------------------- forward (Section 2, Section 5.1)
 //
 // One launch for all tables.  A wavefront takes a block of consecutive bags (bag id = t*B + b) and

@@ -39,7 +39,7 @@ EXPORTED = [
     "tbe_backward_rowwise_adagrad", "tbe_backward_adagrad", "tbe_backward_adam", "tbe_backward_sort",
     "tbe_backward_update_rowwise_adagrad", "tbe_backward_update_adagrad", "tbe_backward_update_adam",
     "tbe_backward_artifacts", "tbe_check_inputs",
-    "tbe_profile_enable", "tbe_profile_read", "tbe_status_string", "tbe_last_hip_error",
+    "tbe_profile_enable", "tbe_profile_read", "tbe_probe_read", "tbe_status_string", "tbe_last_hip_error",
 ]
 # include/tbe_inputs.h
 EXPORTED_INPUTS = [
@@ -100,6 +100,7 @@ def lib() -> ctypes.CDLL:
         L.tbe_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64),
                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         sz = ctypes.c_size_t
+        L.tbe_probe_read.argtypes = [vp, sz, i32, vp, vp]
         L.tbe_inputs_scratch_bytes.argtypes = [i64]
         L.tbe_lengths_to_offsets.argtypes = [vp, i64, vp, vp, sz, vp]
         L.tbe_lengths_to_offsets_noalloc.argtypes = [vp, i64, vp, vp]
@@ -239,6 +240,10 @@ def tbe_profile_read(h) -> Tuple[int, Dict[str, Tuple[int, float]]]:
         for i in range(n.value):
             out[names[i].decode()] = (int(launches[i]), float(ms[i]))
     return rc, out
+
+
+def tbe_probe_read(src: torch.Tensor, nbytes: int, passes: int, sink: torch.Tensor, stream=None) -> int:
+    return lib().tbe_probe_read(_ptr(src), ctypes.c_size_t(nbytes), int(passes), _ptr(sink), _stream_ptr(stream))
 
 
 def tbe_last_hip_error(h) -> str:

@@ -218,3 +218,23 @@ def test_well_conditioned_case_meets_plain_relative_tolerance(gpu_device, dtype)
     assert rel_w.max() <= tl.rtol_for(dtype)
     assert rel_m.max() <= tl.RTOL_FP32
     op.close()
+
+
+def test_read_probe_runs_and_touches_nothing(gpu_device):
+    """The read-rate probe of the C-ABI: enqueues on the given stream, reads only, and leaves source and sink as
+    they were (the sink is written for one xor value in 2^32 only; this buffer's xor is not that value)."""
+    import torch
+
+    n = (8 << 20) // 4 + 12                      # a ragged tail beyond the last 16-byte word
+    src = torch.arange(n, dtype=torch.int32, device=gpu_device)
+    before = src.clone()
+    sink = torch.full((1,), 77, dtype=torch.int32, device=gpu_device)
+    for passes in (1, 3):
+        assert tbe.tbe_probe_read(src, 4 * n, passes, sink) == tbe.TBE_OK
+    s2 = torch.cuda.Stream()
+    with torch.cuda.stream(s2):
+        assert tbe.tbe_probe_read(src, 4 * n, 2, sink, stream=s2) == tbe.TBE_OK
+    torch.cuda.synchronize()
+    assert torch.equal(src, before) and int(sink.item()) == 77
+    assert tbe.tbe_probe_read(src, 16, 1, sink) == tbe.TBE_OK      # a single word
+    torch.cuda.synchronize()

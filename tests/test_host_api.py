@@ -135,6 +135,17 @@ def test_input_side_entry_points_validate_on_the_host():
                                    None) == tbe.TBE_ERR_UNSUPPORTED
 
 
+def test_read_probe_validates_its_arguments_on_the_host():
+    L = tbe.lib()
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    assert L.tbe_probe_read(None, sz(1 << 20), 1, vp(256), None) == tbe.TBE_ERR_INVALID_ARG      # null source
+    assert L.tbe_probe_read(vp(256), sz(1 << 20), 1, None, None) == tbe.TBE_ERR_INVALID_ARG      # null sink
+    assert L.tbe_probe_read(vp(264), sz(1 << 20), 1, vp(256), None) == tbe.TBE_ERR_INVALID_ARG   # source not 16-aligned
+    assert L.tbe_probe_read(vp(256), sz(8), 1, vp(256), None) == tbe.TBE_ERR_INVALID_ARG         # less than one word
+    assert L.tbe_probe_read(vp(256), sz(1 << 20), 0, vp(256), None) == tbe.TBE_ERR_INVALID_ARG   # no pass
+    assert L.tbe_probe_read(vp(256), sz(1 << 20), 1, vp(258), None) == tbe.TBE_ERR_INVALID_ARG   # sink not 4-aligned
+
+
 def test_optimizer_and_dtype_configuration():
     rows, dims = [10, 3], [8, 4]
     elems = 10 * 8 + 3 * 4
