@@ -130,8 +130,9 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0,
     ndense_t / udense_t: the same for the runs beyond the dense threshold, which dense_rows_kernel sums; so / sg: bytes per output / gradient element; state_per_elem: float32 optimizer
     states per weight element (0 = one moment per row); passes_t: radix passes per table (default: one pass for
     every table, the figure per pass).
-    Sort figures are per launch: the first scatter pass reads the caller's 4-byte indices and writes key + payload
-    (12 bytes per lookup), later passes read and write both (16 bytes)."""
+    Sort figures are per launch: a table's first scatter pass reads the caller's 4-byte indices and writes key +
+    payload, later passes read and write both; between the passes the payload is 2 bytes while the batch is at most
+    65536 (10 / 12 / 14 bytes per lookup in a first / middle / last pass, 12 in an only pass), else 4 (12 / 16 / 16)."""
     sw = 4 if spec.dtype == 0 else 2
     D = spec.dims.astype(np.float64)
     B = float(spec.batch)
@@ -152,7 +153,11 @@ def kernel_bytes(spec, n_t, u_t, nlong_t, ulong_t, so=4, sg=4, state_per_elem=0,
         hist = N * 4
     else:
         launches = float(np.max(passes_t))
-        scatter = float((n_t * (12 + 16 * (passes_t - 1))).sum()) / launches
+        if spec.batch <= 65536:
+            per_lookup = np.where(passes_t <= 1, 12.0, 10.0 + 12.0 * (passes_t - 2) + 14.0)
+        else:
+            per_lookup = 12.0 + 16.0 * (passes_t - 1)
+        scatter = float((n_t * per_lookup).sum()) / launches
         hist = float((n_t * 4 * passes_t).sum()) / launches
     comp = {
         "forward": float((u_t * D * sw).sum() + io_fwd),

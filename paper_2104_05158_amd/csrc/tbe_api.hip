@@ -591,14 +591,20 @@ static tbe_status_t enqueue_sort(tbe_s* h, const int32_t* d_indices, const int64
         }
         {
             ScopedTimer tm(h, SLOT_RADIX_SCATTER, st);
-            if (p == passes - 1)
-                hipLaunchKernelGGL((radix_scatter_kernel<true>), dim3(max_tiles), dim3(kSortThreads), 0, st, pl, meta,
-                                   keys_cur, vals_cur, indices, keys[out], vals[out], hist, d_offsets, row_base, batch,
-                                   p, passes, nd_bits);
+            // a bag number below 2^16 travels as 16 bits between the passes
+            auto launch = [&](auto kernel) {
+                hipLaunchKernelGGL(kernel, dim3(max_tiles), dim3(kSortThreads), 0, st, pl, meta, keys_cur, vals_cur,
+                                   indices, keys[out], vals[out], hist, d_offsets, row_base, batch, p, passes, nd_bits);
+            };
+            const bool last = p == passes - 1, v16 = batch <= 65536;
+            if (last && v16)
+                launch(radix_scatter_kernel<true, true>);
+            else if (last)
+                launch(radix_scatter_kernel<true, false>);
+            else if (v16)
+                launch(radix_scatter_kernel<false, true>);
             else
-                hipLaunchKernelGGL((radix_scatter_kernel<false>), dim3(max_tiles), dim3(kSortThreads), 0, st, pl, meta,
-                                   keys_cur, vals_cur, indices, keys[out], vals[out], hist, d_offsets, row_base, batch,
-                                   p, passes, nd_bits);
+                launch(radix_scatter_kernel<false, false>);
             TBE_LAUNCH_CHECK(h, "radix_scatter_kernel");
         }
         cur = out;

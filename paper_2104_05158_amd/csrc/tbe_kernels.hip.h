@@ -628,8 +628,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
 
 // A table's first pass reads the caller's index array as keys and computes the payload from the offsets;
 // LAST (the launch in which every table makes its last pass): the table's row base is added to the keys
-// that are written out.
-template <bool LAST>
+// that are written out.  V16 (batch <= 65536): between the passes the payload, a bag number below 2^16,
+// travels as 16 bits (in the same buffers); the last launch writes the int32 payloads the update reads.
+template <bool LAST, bool V16>
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     SortPlan pl, const TableMeta* __restrict__ meta, const uint32_t* __restrict__ keys_cur,
     const int32_t* __restrict__ vals_in, const uint32_t* __restrict__ indices,
@@ -673,7 +674,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
         const int q = min(base + r * kWave + lane, end - 1);
         key[r] = keys_in[q];
         if (!FIRST)
-            val[r] = vals_in[q];
+            val[r] = V16 ? (int32_t)reinterpret_cast<const uint16_t*>(vals_in)[q] : vals_in[q];
     }
     if (FIRST) {
         // payload = bag of the position: the borders of the bags the tile touches are staged in
@@ -797,7 +798,10 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             const uint32_t k = s_keys[p];
             const uint32_t g = s_goff[(k >> shift) & mask] + (uint32_t)p;
             keys_out[g] = k + add;
-            vals_out[g] = s_vals[p];
+            if (V16 && !LAST)
+                reinterpret_cast<uint16_t*>(vals_out)[g] = (uint16_t)s_vals[p];
+            else
+                vals_out[g] = s_vals[p];
         }
     }
 }

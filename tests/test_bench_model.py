@@ -56,9 +56,17 @@ def test_sort_bytes_per_launch_follow_the_tables_pass_counts():
     spec = wl.custom([300, 70000], [8, 16], 1, 4, 1.0)
     n_t, u_t = np.array([10.0, 6.0]), np.array([3.0, 6.0])
     comp, _ = bench.kernel_bytes(spec, n_t, u_t, np.zeros(2), np.zeros(2), passes_t=bench.sort_passes(spec.rows))
-    # three launches; the first pass of a table moves 12 bytes per lookup (index in, key + payload out), later ones 16
-    assert comp["radix_scatter"] == (10 * (12 + 16) + 6 * (12 + 32)) / 3
+    # three launches; batch <= 65536: the payload is 2 bytes between the passes.  First pass of a table: index in,
+    # key + short payload out (10 bytes per lookup); middle pass 6 in + 6 out; last pass 6 in + 8 out
+    assert comp["radix_scatter"] == (10 * (10 + 14) + 6 * (10 + 12 + 14)) / 3
     assert comp["radix_hist"] == (10 * 4 * 2 + 6 * 4 * 3) / 3
+    big = wl.custom([300, 70000], [8, 16], 1, 70000, 1.0)
+    comp, _ = bench.kernel_bytes(big, n_t, u_t, np.zeros(2), np.zeros(2), passes_t=bench.sort_passes(big.rows))
+    assert comp["radix_scatter"] == (10 * (12 + 16) + 6 * (12 + 32)) / 3       # 4-byte payloads beyond 65536 bags
+    one = wl.custom([200], [8], 1, 4, 1.0)
+    comp, _ = bench.kernel_bytes(one, np.array([10.0]), np.array([3.0]), np.zeros(1), np.zeros(1),
+                                 passes_t=bench.sort_passes(one.rows))
+    assert comp["radix_scatter"] == 10 * 12                                     # an only pass: index in, key + payload out
 
 
 def test_default_invocation_is_config_4_with_3_and_2_alongside():

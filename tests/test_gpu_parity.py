@@ -109,6 +109,21 @@ def test_tables_with_different_pass_counts_in_one_sort(gpu_device):
     tl.full_parity_step(spec, idx, off, w, g, gpu_device, what="mixed_passes")
 
 
+@pytest.mark.parametrize("batch", [65536, 65537, 70_000])
+def test_sort_payloads_at_and_beyond_16_bits(gpu_device, batch):
+    # the sort carries the bag number as 16 bits between its passes while the batch allows it (65536: the last bag
+    # is 65535) and as 32 bits beyond; tables of 1, 2 and 3 passes; the last bags carry lookups of the extreme rows
+    rows = [200, 300, 70_000]
+    spec = wl.custom(rows, [4, 8, 4], 0, batch, [0.6, 0.9, 0.7], name=f"payload{batch}")
+    idx, off, w, g = _np_case(spec, 31)
+    for t in range(3):
+        lo, hi = int(off[(t + 1) * batch - 1]), int(off[(t + 1) * batch])
+        if hi > lo:
+            idx[hi - 1] = rows[t] - 1
+    assert int(off[-1]) > 3 * 8192
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, what=f"payload{batch}")
+
+
 def test_segmented_sort_tables_without_lookups(gpu_device):
     # tables 0, 2 and 4 receive no lookup at all: they own no sort tile and their rows stay untouched
     spec = wl.custom([50, 3000, 7, 120, 9000], [8, 16, 4, 32, 8], 0, 300, [0.0, 40.0, 0.0, 12.0, 0.0],
