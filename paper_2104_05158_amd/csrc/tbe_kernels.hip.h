@@ -258,6 +258,7 @@ __global__ __launch_bounds__(kFwdThreads) void forward_kernel(
         // fp32 tables: one accumulator per load slot, added pairwise at the end -- the rounding error of a
         // long bag grows with the number of terms each accumulator sees.  (Sums of fp16 values in fp32 are
         // exact for thousands of terms: one accumulator.)
+        static_assert(kFwdUnroll == 4, "the four accumulators of an fp32 table are added pairwise below");
         constexpr int NACC = sizeof(WT) == 4 ? kFwdUnroll : 1;
         float accs[NACC][KMAX][EPL];
 #pragma unroll
@@ -1402,7 +1403,6 @@ __global__ __launch_bounds__(kBwdThreads) void reduce_update_kernel(BwdArgs a)
     // element-wise optimizers carry whole state rows and take one run per group
     constexpr int kNB1 = OPT != kOptRowwiseAdagrad ? 1 : sizeof(WT) == 2 ? 4 : 2;   // runs of one lookup per group
     constexpr int kNB2 = OPT != kOptRowwiseAdagrad ? 1 : 2;                          // runs of two lookups per group
-    static_assert(kFwdUnroll == 4, "the forward adds its four accumulators pairwise");
     static_assert(kSpan <= 256, "run indices of a span are kept in bytes");
     static_assert(kShortRun == 4, "run_batch is instantiated for 1..4 lookups");
     __shared__ int32_t s_seg_all[kWaves][kSegCap];
