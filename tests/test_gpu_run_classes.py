@@ -86,3 +86,15 @@ def test_other_optimizers_and_16bit_gradients_over_the_classes(gpu_device):
     tl.assert_artifacts_equal(op.artifacts(), ref["art"], "bf16")
     tl.assert_update_close(spec, ref, w0, m0, op.weights.cpu().numpy(), op.state.cpu().numpy(), 0.01, 1e-8, "bf16")
     op.close()
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_spans_of_single_lookup_rows_only(gpu_device, dtype):
+    # every row once: a span holds 256 runs of one lookup, and for D = 4 (64 lane groups) one step takes all of
+    # them; 1000 rows leave a ragged last span; a second table of two-lookup rows fills the two-runs-per-group steps
+    dims = [4, 8, 64, 128, 512]
+    lens = [np.ones(1000, np.int64) for _ in dims] + [np.full(700, 2, np.int64)]
+    spec, idx, off = _explicit_case(dims + [16], lens, batch=29, seed=31 + dtype, dtype=dtype)
+    w = wl.make_weights(spec, "cpu", seed=32).numpy()
+    g = wl.make_grad(spec, "cpu", seed=33).numpy()
+    tl.full_parity_step(spec, idx, off, w, g, gpu_device, lr=0.03, what="single-lookup rows")
